@@ -1,0 +1,166 @@
+/*
+ * libdass -- the data-parallel hot path of DaSS pruning for GLU-variant MLPs
+ * (Guo et al., "Dependency-aware Semi-structured Sparsity of GLU Variants in
+ * Large Language Models", arXiv 2405.01943) on AMD gfx950.
+ *
+ * C ABI: plain pointers and sizes only.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises.  Work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and calls are ordered by that stream.
+ *   - Matrices are row-major in the paper's transposed layout (Sec. 3):
+ *     Gate-Proj and Up-Proj are [d_int, d_hidden], Down-Proj is
+ *     [d_hidden, d_int]; `ld*` is the row stride in elements.
+ *   - Data pointers must be 16-byte aligned and row strides a multiple of
+ *     8 elements (bf16) or 4 elements (f32); otherwise DASS_ERR_ALIGN.
+ *   - All argument checks happen on the host before the first HIP call, so a
+ *     rejected call has touched nothing.
+ *   - Inputs must be finite.  The result for NaN or Inf inputs is undefined.
+ *   - Thread safe; the only library state is a thread-local error string.
+ */
+#ifndef DASS_H
+#define DASS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DASS_OK = 0,
+    DASS_ERR_NULL = 1,      /* a required pointer is NULL                        */
+    DASS_ERR_SHAPE = 2,     /* non-positive size, ld < width, ragged group axis  */
+    DASS_ERR_DTYPE = 3,     /* dtype or activation enum out of range             */
+    DASS_ERR_ARG = 4,       /* bad (n_keep, m), alpha, n_prune                   */
+    DASS_ERR_ALIGN = 5,     /* pointer or stride alignment                       */
+    DASS_ERR_WORKSPACE = 6, /* workspace missing or too small                    */
+    DASS_ERR_HIP = 7        /* a HIP launch failed; see dass_last_error_string() */
+} dass_status;
+
+typedef enum { DASS_F32 = 0, DASS_BF16 = 1 } dass_dtype;
+
+/* sigma(.) of Sec. 2.2 Eq. 2: Swish (beta = 1) for SwiGLU, GeLU (tanh or erf
+ * form) for GeGLU, ReLU for ReGLU. */
+typedef enum {
+    DASS_ACT_SILU = 0,
+    DASS_ACT_GELU_TANH = 1,
+    DASS_ACT_GELU_ERF = 2,
+    DASS_ACT_RELU = 3
+} dass_act;
+
+/* A dimension of a row-major matrix W[rows, cols]. */
+typedef enum { DASS_AXIS_ROWS = 0, DASS_AXIS_COLS = 1 } dass_axis;
+
+/*
+ * Stage 1 -- calibration statistics (Sec. 2.2 Eq. 2 and Sec. 3 "Incorporating
+ * Dependency into Weight Importance": the group-importance indicator is the L2
+ * norm of the intermediate activation y, taken over all calibration tokens).
+ *
+ *   for every intermediate neuron i:
+ *     sumsq[i] (+)= sum over t of ( act(X[t,:] . Wgate[i,:]) * (X[t,:] . Wup[i,:]) )^2
+ *     norms_out[i] = sqrt(sumsq[i])                          (if norms_out != NULL)
+ *
+ * The products X Wgate^T and X Wup^T are accumulated in f32 and y is never
+ * written to memory.
+ *
+ *   X      [T, d]      row stride ldx, read only, dtype dt
+ *   Wgate  [d_int, d]  row stride ldw, read only, dtype dt
+ *   Wup    [d_int, d]  row stride ldw, read only, dtype dt
+ *   sumsq  [d_int] f32, in/out: the only carried state.  accumulate = 0
+ *          overwrites it, accumulate = 1 adds this call's tokens to it, so a
+ *          calibration set can be streamed in chunks (or resumed from a saved
+ *          copy of sumsq).
+ *   norms_out [d_int] f32 or NULL.
+ *   workspace  device scratch of at least dass_calib_workspace_bytes() bytes
+ *          (may be NULL when that is 0).
+ *
+ * d must be a multiple of 8 (bf16) or 4 (f32).  T, d_int are arbitrary positive.
+ * The accumulation over tokens uses f32 atomics, so results can differ in the
+ * last bits from run to run.
+ */
+size_t dass_calib_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt);
+
+dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx,
+                             const void *Wgate, const void *Wup, int64_t ldw,
+                             int64_t d, int64_t d_int, dass_dtype dt, dass_act act,
+                             float *sumsq, int accumulate, float *norms_out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Stage 2 -- DaSS scoring with N:M selection (Sec. 3 Eq. 4, Eq. 5 and
+ * "Extension to N:M Sparsity").
+ *
+ *   score[r, c] = |W[r, c]| * f[k],  f = norms^alpha,
+ *                 k = r if norm_axis = ROWS, c if norm_axis = COLS
+ *
+ * In every group of m consecutive positions along group_axis (groups start at
+ * index 0) the n_keep positions of highest score are left untouched and the
+ * other m - n_keep are overwritten with +0, IN PLACE.  Equal scores: the lower
+ * index along the group is kept.  Scores are compared exactly (as the real
+ * product of the stored weight and the f32 factor), never after rounding.
+ *
+ * DaSS uses  Gate/Up: norm_axis = group_axis = ROWS, alpha = 0.5  (Eq. 4,
+ *                     input-balanced groups: m consecutive neurons per input)
+ *            Down:    norm_axis = group_axis = COLS, alpha = 1    (Eq. 5,
+ *                     output-balanced groups).
+ *
+ *   W      [rows, cols] row stride ld, dtype dt, modified in place
+ *   norms  f32, length rows (norm_axis = ROWS) or cols (COLS), read only
+ *   alpha  finite, >= 0.  f = 1 for alpha = 0 (also where the norm is 0),
+ *          norms for alpha = 1, the correctly rounded f32 square root for 0.5,
+ *          otherwise pow() evaluated in f64 and rounded to f32.
+ *   m in {2, 4, 8, 16}, 0 < n_keep < m; the length of group_axis must be a
+ *          multiple of m (else DASS_ERR_SHAPE); cols must be a multiple of 8.
+ *   mask_out NULL, or rows * (cols / 8) bytes: bit (c & 7) of byte c / 8 of
+ *          row r is 1 iff W[r, c] was kept.
+ *   workspace  device scratch of at least dass_nm_workspace_bytes() bytes,
+ *          16-byte aligned; it receives the factor vector f.  Calls that run
+ *          concurrently on different streams need separate workspaces.
+ */
+size_t dass_nm_workspace_bytes(int64_t rows, int64_t cols, dass_axis norm_axis);
+
+dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, int64_t ld, dass_dtype dt,
+                               const float *norms, dass_axis norm_axis, dass_axis group_axis,
+                               double alpha, int n_keep, int m, uint8_t *mask_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Stage 2 -- DaSS scoring with per-line unstructured selection (Sec. 3
+ * "Pruning Granularity": weights are compared for each input individually for
+ * Gate/Up, for each output individually for Down, and the lowest scores of
+ * each comparison group are pruned).
+ *
+ * Every full line along group_axis (a column of W when group_axis = ROWS, a
+ * row when group_axis = COLS) is one comparison group.  Its n_prune positions
+ * of lowest score are overwritten with +0 in place; among equal scores the
+ * higher index is pruned first.  Scores, factor, mask_out as above; the caller
+ * converts a sparsity ratio s to n_prune = floor(s * line length).
+ *
+ *   workspace  device scratch of at least dass_unstructured_workspace_bytes()
+ *              bytes, 16-byte aligned (holds f and the per-line selection state).
+ */
+size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, dass_dtype dt,
+                                         dass_axis norm_axis, dass_axis group_axis);
+
+dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, int64_t ld,
+                                         dass_dtype dt, const float *norms,
+                                         dass_axis norm_axis, dass_axis group_axis,
+                                         double alpha, int64_t n_prune, uint8_t *mask_out,
+                                         void *workspace, size_t workspace_bytes,
+                                         void *hip_stream);
+
+/* Name of a status code; never NULL. */
+const char *dass_status_string(dass_status s);
+/* Detail of the calling thread's most recent failed call ("" if none). */
+const char *dass_last_error_string(void);
+/* Library version, major * 10000 + minor * 100 + patch. */
+int dass_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASS_H */

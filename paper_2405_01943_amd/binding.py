@@ -1,0 +1,199 @@
+"""ctypes binding of libdass.so -- argument marshalling only.
+
+Function names follow the C ABI in ``include/dass.h`` (``dass_`` prefix
+dropped).  Tensors are torch CUDA tensors; their ``data_ptr()`` and the current
+torch stream are handed to the library, which does all the work.  There is no
+fallback: if the shared library cannot be loaded the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdass.so")
+
+DTYPE = {torch.float32: 0, torch.bfloat16: 1}
+ACT = {"silu": 0, "gelu_tanh": 1, "gelu_erf": 2, "relu": 3}
+AXIS = {"rows": 0, "cols": 1}
+
+EXPORTS = (
+    "dass_calib_workspace_bytes", "dass_calib_norms",
+    "dass_nm_workspace_bytes", "dass_score_mask_nm",
+    "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
+    "dass_status_string", "dass_last_error_string", "dass_version",
+)
+
+
+class DassError(RuntimeError):
+    """A libdass call returned a status other than DASS_OK."""
+
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name}: {detail}" if detail else name)
+        self.status = status
+        self.status_name = name
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdass.so (building it with hipcc only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, sz, vp, ci, dbl = (ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int,
+                            ctypes.c_double)
+    lib.dass_calib_workspace_bytes.restype = sz
+    lib.dass_calib_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.dass_calib_norms.restype = ci
+    lib.dass_calib_norms.argtypes = [vp, i64, i64, vp, vp, i64, i64, i64, ci, ci, vp, ci, vp,
+                                     vp, sz, vp]
+    lib.dass_nm_workspace_bytes.restype = sz
+    lib.dass_nm_workspace_bytes.argtypes = [i64, i64, ci]
+    lib.dass_score_mask_nm.restype = ci
+    lib.dass_score_mask_nm.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, ci, ci, vp,
+                                       vp, sz, vp]
+    lib.dass_unstructured_workspace_bytes.restype = sz
+    lib.dass_unstructured_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
+    lib.dass_score_mask_unstructured.restype = ci
+    lib.dass_score_mask_unstructured.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, i64, vp,
+                                                 vp, sz, vp]
+    lib.dass_status_string.restype = ctypes.c_char_p
+    lib.dass_status_string.argtypes = [ci]
+    lib.dass_last_error_string.restype = ctypes.c_char_p
+    lib.dass_last_error_string.argtypes = []
+    lib.dass_version.restype = ci
+    lib.dass_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().dass_version())
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        lib = load_library()
+        raise DassError(status, lib.dass_status_string(status).decode(),
+                        lib.dass_last_error_string().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _matrix(t: torch.Tensor, name: str):
+    if t.dim() != 2 or t.stride(1) != 1 or t.dtype not in DTYPE:
+        raise TypeError(f"{name}: need a 2-D f32/bf16 tensor with unit column stride")
+    return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def _scratch(nbytes: int, device) -> Optional[torch.Tensor]:
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------ stage 1 --
+def calib_workspace_bytes(T: int, d: int, d_int: int, dtype: torch.dtype) -> int:
+    return int(load_library().dass_calib_workspace_bytes(T, d, d_int, DTYPE[dtype]))
+
+
+def calib_norms(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, act: str,
+                sumsq: torch.Tensor, accumulate: bool = False,
+                norms_out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_calib_norms: sumsq (+)= sum_t y[t, :]^2 with y = act(X Wgate^T) * (X Wup^T)."""
+    lib = load_library()
+    T, d, ldx = _matrix(X, "X")
+    d_int, dg, ldw = _matrix(Wgate, "Wgate")
+    d_int_u, du, ldw_u = _matrix(Wup, "Wup")
+    if (d_int_u, du, ldw_u) != (d_int, dg, ldw) or dg != d or not (X.dtype == Wgate.dtype == Wup.dtype):
+        raise ValueError("X, Wgate, Wup disagree in shape, stride or dtype")
+    if sumsq.dtype != torch.float32 or sumsq.numel() != d_int or not sumsq.is_contiguous():
+        raise TypeError("sumsq: need contiguous float32[d_int]")
+    if norms_out is not None and (norms_out.dtype != torch.float32 or norms_out.numel() != d_int
+                                  or not norms_out.is_contiguous()):
+        raise TypeError("norms_out: need contiguous float32[d_int]")
+    need = int(lib.dass_calib_workspace_bytes(T, d, d_int, DTYPE[X.dtype]))
+    if workspace is None and need > 0:
+        workspace = _scratch(need, X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.dass_calib_norms(_ptr(X), T, ldx, _ptr(Wgate), _ptr(Wup), ldw, d, d_int,
+                                DTYPE[X.dtype], ACT[act], _ptr(sumsq), int(bool(accumulate)),
+                                _ptr(norms_out), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+# ------------------------------------------------------------------ stage 2 --
+def nm_workspace_bytes(rows: int, cols: int, norm_axis: str) -> int:
+    return int(load_library().dass_nm_workspace_bytes(rows, cols, AXIS[norm_axis]))
+
+
+def score_mask_nm(W: torch.Tensor, norms: torch.Tensor, norm_axis: str, group_axis: str,
+                  alpha: float, n_keep: int, m: int, mask_out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_score_mask_nm: in-place N:M pruning of W by |W| * norms^alpha."""
+    lib = load_library()
+    rows, cols, ld = _matrix(W, "W")
+    if norms.dtype != torch.float32 or not norms.is_contiguous():
+        raise TypeError("norms: need contiguous float32")
+    if norms.numel() != (rows if norm_axis == "rows" else cols):
+        raise ValueError("norms length does not match norm_axis")
+    if mask_out is not None and (mask_out.dtype != torch.uint8 or not mask_out.is_contiguous()
+                                 or mask_out.numel() != rows * (cols // 8)):
+        raise TypeError("mask_out: need contiguous uint8[rows * cols / 8]")
+    need = int(lib.dass_nm_workspace_bytes(rows, cols, AXIS[norm_axis]))
+    if workspace is None:
+        workspace = _scratch(need, W.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.dass_score_mask_nm(_ptr(W), rows, cols, ld, DTYPE[W.dtype], _ptr(norms),
+                                  AXIS[norm_axis], AXIS[group_axis], float(alpha), int(n_keep),
+                                  int(m), _ptr(mask_out), _ptr(workspace), ws_bytes,
+                                  _stream(stream)))
+
+
+def unstructured_workspace_bytes(rows: int, cols: int, dtype: torch.dtype, norm_axis: str,
+                                 group_axis: str) -> int:
+    return int(load_library().dass_unstructured_workspace_bytes(
+        rows, cols, DTYPE[dtype], AXIS[norm_axis], AXIS[group_axis]))
+
+
+def score_mask_unstructured(W: torch.Tensor, norms: torch.Tensor, norm_axis: str, group_axis: str,
+                            alpha: float, n_prune: int, mask_out: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_score_mask_unstructured: prune the n_prune lowest scores of every line."""
+    lib = load_library()
+    rows, cols, ld = _matrix(W, "W")
+    if norms.dtype != torch.float32 or not norms.is_contiguous():
+        raise TypeError("norms: need contiguous float32")
+    if norms.numel() != (rows if norm_axis == "rows" else cols):
+        raise ValueError("norms length does not match norm_axis")
+    if mask_out is not None and (mask_out.dtype != torch.uint8 or not mask_out.is_contiguous()
+                                 or mask_out.numel() != rows * (cols // 8)):
+        raise TypeError("mask_out: need contiguous uint8[rows * cols / 8]")
+    need = int(lib.dass_unstructured_workspace_bytes(rows, cols, DTYPE[W.dtype], AXIS[norm_axis],
+                                                     AXIS[group_axis]))
+    if workspace is None:
+        workspace = _scratch(need, W.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.dass_score_mask_unstructured(_ptr(W), rows, cols, ld, DTYPE[W.dtype], _ptr(norms),
+                                            AXIS[norm_axis], AXIS[group_axis], float(alpha),
+                                            int(n_prune), _ptr(mask_out), _ptr(workspace), ws_bytes,
+                                            _stream(stream)))

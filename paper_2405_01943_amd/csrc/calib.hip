@@ -1,0 +1,449 @@
+// Stage 1: calibration statistics.  For every intermediate neuron i
+//     sumsq[i] (+)= sum_t ( act(x_t . Wgate_i) * (x_t . Wup_i) )^2
+// i.e. the GLU product of Sec. 2.2 Eq. 2 reduced to the squared L2 norm that
+// Sec. 3 uses as the group-importance indicator, over all calibration tokens.
+// The two projections are dense contractions; y lives only in accumulators.
+//
+// bf16: MFMA kernel.  A workgroup owns a BM-token x BN-neuron tile and keeps a
+// gate and an up accumulator for it; X, Wgate and Wup slabs of BK columns are
+// staged through double-buffered LDS (16-byte chunks, XOR-swizzled so that the
+// 16-byte fragment reads of a wavefront spread over all banks).  Tokens are the
+// MFMA "M" index and neurons the "N" index, so the 16 accumulator registers a
+// lane holds for one 32x32 block belong to ONE neuron and 16 tokens: the sum
+// over tokens starts as plain register adds, then one cross-lane add, then one
+// f32 atomic per neuron and wavefront.
+//
+// f32: a plain LDS-tiled FMA kernel (small shapes).
+#include "dass_internal.h"
+
+namespace dass {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+struct alignas(16) Chunk {
+    uint32_t w[4];
+};
+
+// ------------------------------------------------------------- activations --
+template <int ACT>
+__device__ __forceinline__ float glu_act_fast(float g)
+{
+    if constexpr (ACT == DASS_ACT_SILU) {
+        return __fdividef(g, 1.0f + __expf(-g));
+    } else if constexpr (ACT == DASS_ACT_GELU_TANH) {
+        // 0.5 g (1 + tanh z) = g / (1 + exp(-2 z)),  z = sqrt(2/pi) (g + 0.044715 g^3)
+        const float z2 = 1.5957691216057308f * g * (1.0f + 0.044715f * g * g);
+        return __fdividef(g, 1.0f + __expf(-z2));
+    } else if constexpr (ACT == DASS_ACT_GELU_ERF) {
+        return 0.5f * g * (1.0f + erff(g * 0.7071067811865476f));
+    } else {
+        return fmaxf(g, 0.0f);
+    }
+}
+
+__device__ __forceinline__ float glu_act_precise(float g, int act)
+{
+    switch (act) {
+    case DASS_ACT_SILU:
+        return g / (1.0f + expf(-g));
+    case DASS_ACT_GELU_TANH: {
+        const float z2 = 1.5957691216057308f * g * (1.0f + 0.044715f * g * g);
+        return g / (1.0f + expf(-z2));
+    }
+    case DASS_ACT_GELU_ERF:
+        return 0.5f * g * (1.0f + erff(g * 0.7071067811865476f));
+    default:
+        return fmaxf(g, 0.0f);
+    }
+}
+
+// ------------------------------------------------------- small helper kernels --
+__global__ void fill_zero_kernel(float *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0.0f;
+}
+
+__global__ void sqrt_kernel(const float *__restrict__ sumsq, float *__restrict__ norms, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        norms[i] = (float)sqrt((double)sumsq[i]);
+}
+
+// ------------------------------------------------------------------ bf16 MFMA --
+// Position (in 16-byte chunks) of chunk c of tile row r inside the row's BK/8
+// chunk slots.  Rows r and r+8 share a parity, so the extra bit keeps any 16
+// consecutive rows of one chunk column on distinct (row parity, slot) pairs.
+template <int CHUNKS>
+__device__ __forceinline__ int swizzle(int r, int c)
+{
+    return c ^ (((r & 7) ^ ((r >> 3) & 1)) & (CHUNKS - 1));
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int ACT>
+__global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
+    const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
+    const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
+    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n)
+{
+    constexpr int NT = 64 * WM * WN;       // threads
+    constexpr int CH = BK / 8;             // 16-byte chunks per tile row
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int A_CHUNKS = BM * CH / NT;  // chunks per thread per slab
+    constexpr int B_CHUNKS = BN * CH / NT;  // per matrix
+    constexpr int ROWS_PER_PASS = NT / CH;
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    constexpr int STAGE = A_BYTES + 2 * B_BYTES;
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && BK % 16 == 0, "tile shape");
+    static_assert((BM * CH) % NT == 0 && (BN * CH) % NT == 0, "staging split");
+    static_assert(CH == 4 || CH == 8, "swizzle assumes 4 or 8 chunks per row");
+
+    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+
+    // ---- tile assignment: consecutive workgroup ids go to different XCDs (8 of
+    // them, each with its own L2); give each XCD a contiguous run of a tile order
+    // in which any 32 consecutive tiles form a 4-token-tile x 8-neuron-tile patch.
+    const int64_t n_tiles = tiles_t * tiles_n;
+    const int64_t per_xcd = (n_tiles + 7) / 8;
+    const int64_t lin = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (lin >= n_tiles)
+        return;
+    constexpr int BAND = 8;
+    const int64_t full_bands = tiles_n / BAND;
+    int64_t tile_t, tile_n;
+    if (lin < full_bands * BAND * tiles_t) {
+        const int64_t band = lin / (BAND * tiles_t), rem = lin % (BAND * tiles_t);
+        tile_t = rem / BAND;
+        tile_n = band * BAND + rem % BAND;
+    } else {
+        const int64_t rem = lin - full_bands * BAND * tiles_t;
+        const int64_t bw = tiles_n - full_bands * BAND;
+        tile_t = rem / bw;
+        tile_n = full_bands * BAND + rem % bw;
+    }
+    const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- global -> register staging: thread owns chunk column (tid % CH) of rows
+    // tid / CH + p * ROWS_PER_PASS.  Out-of-range rows are clamped to the last
+    // valid row: their products are discarded in the epilogue.
+    const int ld_c = tid % CH, ld_r = tid / CH;
+    const uint16_t *a_ptr[A_CHUNKS];
+    const uint16_t *g_ptr[B_CHUNKS];
+    const uint16_t *u_ptr[B_CHUNKS];
+#pragma unroll
+    for (int p = 0; p < A_CHUNKS; ++p) {
+        int64_t r = t0 + ld_r + p * ROWS_PER_PASS;
+        r = r < T ? r : T - 1;
+        a_ptr[p] = X + r * ldx + ld_c * 8;
+    }
+#pragma unroll
+    for (int p = 0; p < B_CHUNKS; ++p) {
+        int64_t r = n0 + ld_r + p * ROWS_PER_PASS;
+        r = r < d_int ? r : d_int - 1;
+        g_ptr[p] = Wg + r * ldw + ld_c * 8;
+        u_ptr[p] = Wu + r * ldw + ld_c * 8;
+    }
+    Chunk a_st[A_CHUNKS], g_st[B_CHUNKS], u_st[B_CHUNKS];
+
+    auto load_slab = [&](int64_t k0) {
+        // the K tail (d not a multiple of BK) is filled with zeros
+        const bool k_ok = k0 + ld_c * 8 < d;
+        const Chunk zero = {{0u, 0u, 0u, 0u}};
+#pragma unroll
+        for (int p = 0; p < A_CHUNKS; ++p)
+            a_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(a_ptr[p] + k0) : zero;
+#pragma unroll
+        for (int p = 0; p < B_CHUNKS; ++p) {
+            g_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(g_ptr[p] + k0) : zero;
+            u_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(u_ptr[p] + k0) : zero;
+        }
+    };
+    auto store_slab = [&](int buf) {
+        char *base = lds + buf * STAGE;
+#pragma unroll
+        for (int p = 0; p < A_CHUNKS; ++p) {
+            const int r = ld_r + p * ROWS_PER_PASS;
+            *reinterpret_cast<Chunk *>(base + (r * CH + swizzle<CH>(r, ld_c)) * 16) = a_st[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_CHUNKS; ++p) {
+            const int r = ld_r + p * ROWS_PER_PASS;
+            const int off = (r * CH + swizzle<CH>(r, ld_c)) * 16;
+            *reinterpret_cast<Chunk *>(base + A_BYTES + off) = g_st[p];
+            *reinterpret_cast<Chunk *>(base + A_BYTES + B_BYTES + off) = u_st[p];
+        }
+    };
+
+    f32x16 acc_g[MI][NI], acc_u[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc_g[i][j][r] = 0.0f;
+                acc_u[i][j][r] = 0.0f;
+            }
+
+    // fragment read positions: lane holds tile row (lane % 32) and the
+    // (lane / 32)-th 8-element K chunk of each 16-wide K step
+    const int fr = lane & 31, fc = lane >> 5;
+
+    const int64_t n_slabs = (d + BK - 1) / BK;
+    load_slab(0);
+    store_slab(0);
+    __syncthreads();
+
+    for (int64_t ks = 0; ks < n_slabs; ++ks) {
+        const int cur = (int)(ks & 1);
+        const bool more = ks + 1 < n_slabs;
+        if (more)
+            load_slab((ks + 1) * BK);
+
+        const char *base = lds + cur * STAGE;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[MI], gf[NI], uf[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const int r = wm * TM + i * 32 + fr;
+                af[i] = *reinterpret_cast<const bf16x8 *>(
+                    base + (r * CH + swizzle<CH>(r, kk * 2 + fc)) * 16);
+            }
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int r = wn * TN + j * 32 + fr;
+                const int off = (r * CH + swizzle<CH>(r, kk * 2 + fc)) * 16;
+                gf[j] = *reinterpret_cast<const bf16x8 *>(base + A_BYTES + off);
+                uf[j] = *reinterpret_cast<const bf16x8 *>(base + A_BYTES + B_BYTES + off);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], gf[j],
+                                                                          acc_g[i][j], 0, 0, 0);
+                    acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], uf[j],
+                                                                          acc_u[i][j], 0, 0, 0);
+                }
+        }
+        if (more)
+            store_slab(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens.
+    // Accumulator register r of lane l in a 32x32 block is token row
+    // 8 * (r / 4) + 4 * (l / 32) + r % 4 and neuron column l % 32.
+    const bool full_t = t0 + BM <= T;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        float part = 0.0f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
+                const int64_t t = t0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
+                part += (full_t || t < T) ? y * y : 0.0f;
+            }
+        }
+        part += __shfl_xor(part, 32, 64);
+        const int64_t n = n0 + wn * TN + j * 32 + fr;
+        if (fc == 0 && n < d_int)
+            atomicAdd(sumsq + n, part);
+    }
+}
+
+// ------------------------------------------------------------------ f32 tiled --
+constexpr int F_BM = 64, F_BN = 64, F_BK = 16, F_PAD = 4;
+
+__global__ __launch_bounds__(256) void calib_f32_kernel(
+    const float *__restrict__ X, int64_t T, int64_t ldx, const float *__restrict__ Wg,
+    const float *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int, int act,
+    float *__restrict__ sumsq, int64_t tiles_n)
+{
+    __shared__ float xs[F_BK][F_BM + F_PAD];
+    __shared__ float gs[F_BK][F_BN + F_PAD];
+    __shared__ float us[F_BK][F_BN + F_PAD];
+    __shared__ float red[16][F_BN];
+
+    const int64_t tile_t = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+    const int64_t t0 = tile_t * F_BM, n0 = tile_n * F_BN;
+    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    const int lr = tid / 4, lk = (tid % 4) * 4;  // staging: row lr, columns lk..lk+3
+
+    float ag[4][4], au[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            ag[i][j] = au[i][j] = 0.0f;
+
+    for (int64_t k0 = 0; k0 < d; k0 += F_BK) {
+        const bool k_ok = k0 + lk < d;  // d is a multiple of 4
+        float4 xv = make_float4(0.f, 0.f, 0.f, 0.f), gv = xv, uv = xv;
+        if (k_ok && t0 + lr < T)
+            xv = *reinterpret_cast<const float4 *>(X + (t0 + lr) * ldx + k0 + lk);
+        if (k_ok && n0 + lr < d_int) {
+            gv = *reinterpret_cast<const float4 *>(Wg + (n0 + lr) * ldw + k0 + lk);
+            uv = *reinterpret_cast<const float4 *>(Wu + (n0 + lr) * ldw + k0 + lk);
+        }
+        __syncthreads();  // previous slab fully consumed
+        xs[lk + 0][lr] = xv.x; xs[lk + 1][lr] = xv.y; xs[lk + 2][lr] = xv.z; xs[lk + 3][lr] = xv.w;
+        gs[lk + 0][lr] = gv.x; gs[lk + 1][lr] = gv.y; gs[lk + 2][lr] = gv.z; gs[lk + 3][lr] = gv.w;
+        us[lk + 0][lr] = uv.x; us[lk + 1][lr] = uv.y; us[lk + 2][lr] = uv.z; us[lk + 3][lr] = uv.w;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < F_BK; ++k) {
+            float a[4], g[4], u[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = xs[k][ty * 4 + i];
+                g[i] = gs[k][tx * 4 + i];
+                u[i] = us[k][tx * 4 + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    ag[i][j] = fmaf(a[i], g[j], ag[i][j]);
+                    au[i][j] = fmaf(a[i], u[j], au[i][j]);
+                }
+        }
+    }
+    // tokens past T were staged as zero rows: g = u = 0 gives y = 0
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float y = glu_act_precise(ag[i][j], act) * au[i][j];
+            s = fmaf(y, y, s);
+        }
+        red[ty][tx * 4 + j] = s;
+    }
+    __syncthreads();
+    if (tid < F_BN) {
+        float s = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            s += red[r][tid];
+        if (n0 + tid < d_int)
+            atomicAdd(sumsq + n0 + tid, s);
+    }
+}
+
+// ------------------------------------------------------------------ host side --
+template <int BM, int BN, int BK, int WM, int WN>
+static void launch_mfma(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T,
+                        int64_t ldx, const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d,
+                        int64_t d_int, float *sumsq, int64_t tiles_t, int64_t tiles_n)
+{
+    const dim3 block(64 * WM * WN);
+    switch (act) {
+    case DASS_ACT_SILU:
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_SILU>), grid, block, 0,
+                           stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
+        break;
+    case DASS_ACT_GELU_TANH:
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_GELU_TANH>), grid, block,
+                           0, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
+        break;
+    case DASS_ACT_GELU_ERF:
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_GELU_ERF>), grid, block,
+                           0, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
+        break;
+    default:
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_RELU>), grid, block, 0,
+                           stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
+        break;
+    }
+}
+
+}  // namespace dass
+
+extern "C" size_t dass_calib_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt)
+{
+    (void)T; (void)d; (void)d_int; (void)dt;
+    return 0;  // the accumulation goes straight into sumsq
+}
+
+extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, const void *Wgate,
+                                        const void *Wup, int64_t ldw, int64_t d, int64_t d_int,
+                                        dass_dtype dt, dass_act act, float *sumsq, int accumulate,
+                                        float *norms_out, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_calib_norms";
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!X || !Wgate || !Wup || !sumsq)
+        return fail(DASS_ERR_NULL, "%s: X, Wgate, Wup and sumsq must not be NULL", fn);
+    if (!valid_dtype(dt))
+        return fail(DASS_ERR_DTYPE, "%s: unknown dtype %d", fn, (int)dt);
+    if ((int)act < DASS_ACT_SILU || (int)act > DASS_ACT_RELU)
+        return fail(DASS_ERR_DTYPE, "%s: unknown activation %d", fn, (int)act);
+    if (T <= 0 || d <= 0 || d_int <= 0)
+        return fail(DASS_ERR_SHAPE, "%s: T=%lld d=%lld d_int=%lld must be positive", fn,
+                    (long long)T, (long long)d, (long long)d_int);
+    if (ldx < d || ldw < d)
+        return fail(DASS_ERR_SHAPE, "%s: ldx=%lld, ldw=%lld must be >= d=%lld", fn, (long long)ldx,
+                    (long long)ldw, (long long)d);
+    const int vec = vec_elems(dt);
+    if (d % vec != 0)
+        return fail(DASS_ERR_SHAPE, "%s: d=%lld must be a multiple of %d", fn, (long long)d, vec);
+    if (!aligned16(X) || !aligned16(Wgate) || !aligned16(Wup) ||
+        (reinterpret_cast<uintptr_t>(sumsq) & 3u) ||
+        (norms_out && (reinterpret_cast<uintptr_t>(norms_out) & 3u)))
+        return fail(DASS_ERR_ALIGN, "%s: X, Wgate, Wup must be 16-byte aligned", fn);
+    if (ldx % vec != 0 || ldw % vec != 0)
+        return fail(DASS_ERR_ALIGN, "%s: ldx, ldw must be multiples of %d elements", fn, vec);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const unsigned vgrid = (unsigned)((d_int + 255) / 256);
+    if (!accumulate) {
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(vgrid), dim3(256), 0, stream, sumsq, d_int);
+        dass_status s = check_launch("fill kernel");
+        if (s != DASS_OK)
+            return s;
+    }
+    if (dt == DASS_BF16) {
+        constexpr int BM = 256, BN = 128, BK = 64;
+        const int64_t tiles_t = (T + BM - 1) / BM, tiles_n = (d_int + BN - 1) / BN;
+        const int64_t n_tiles = tiles_t * tiles_n;
+        const int64_t blocks = (n_tiles + 7) / 8 * 8;
+        if (blocks > 0x7fffffffLL)
+            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+        launch_mfma<BM, BN, BK, 2, 2>((int)act, dim3((unsigned)blocks), stream,
+                                      static_cast<const uint16_t *>(X), T, ldx,
+                                      static_cast<const uint16_t *>(Wgate),
+                                      static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
+                                      tiles_t, tiles_n);
+    } else {
+        const int64_t tiles_t = (T + F_BM - 1) / F_BM, tiles_n = (d_int + F_BN - 1) / F_BN;
+        if (tiles_t * tiles_n > 0x7fffffffLL)
+            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+        hipLaunchKernelGGL(calib_f32_kernel, dim3((unsigned)(tiles_t * tiles_n)), dim3(256), 0,
+                           stream, static_cast<const float *>(X), T, ldx,
+                           static_cast<const float *>(Wgate), static_cast<const float *>(Wup), ldw, d,
+                           d_int, (int)act, sumsq, tiles_n);
+    }
+    dass_status s = check_launch("calibration kernel");
+    if (s != DASS_OK)
+        return s;
+    if (norms_out) {
+        hipLaunchKernelGGL(sqrt_kernel, dim3(vgrid), dim3(256), 0, stream, (const float *)sumsq,
+                           norms_out, d_int);
+        s = check_launch("sqrt kernel");
+    }
+    return s;
+}

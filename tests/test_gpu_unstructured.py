@@ -1,0 +1,117 @@
+"""GPU parity: dass_score_mask_unstructured against the float64 oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_01943_amd as dass
+from paper_2405_01943_amd import synth
+
+from gpu_helpers import bits_equal, first_mismatch, padded, to_np32
+
+pytestmark = pytest.mark.gpu
+
+AXES = [("rows", "rows"), ("cols", "cols"), ("rows", "cols"), ("cols", "rows")]
+
+
+def _weights(rows, cols, dtype, device, seed, ties):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    if ties:
+        vals = torch.tensor([-0.5, 0.0, 0.25, 0.5, -0.25, 1.0])
+        w = vals[torch.randint(0, len(vals), (rows, cols), generator=g)]
+    else:
+        w = torch.randn((rows, cols), generator=g) * 0.02
+    return w.to(dtype).to(device)
+
+
+def _norms(n, device, seed, ties):
+    if ties:
+        g = torch.Generator(device="cpu").manual_seed(seed + 1)
+        vals = torch.tensor([0.0, 1.0, 4.0, 16.0, 2.0])
+        return vals[torch.randint(0, len(vals), (n,), generator=g)].to(device)
+    return synth.make_norms(n, "cpu", seed).to(device)
+
+
+def _run_case(gpu_device, rows, cols, dtype, axes, alpha, n_prune, seed, ties=False, pad=0):
+    norm_axis, group_axis = axes
+    W = _weights(rows, cols, dtype, gpu_device, seed, ties)
+    if pad:
+        W = padded(W, pad)
+    nrm = _norms(rows if norm_axis == "rows" else cols, gpu_device, seed, ties)
+    want_w, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), norm_axis,
+                                                 group_axis, alpha, n_prune, want_mask=True)
+    mask = torch.full((rows, cols // 8), 0xAA, dtype=torch.uint8, device=gpu_device)
+    dass.score_mask_unstructured(W, nrm, norm_axis, group_axis, alpha, n_prune, mask_out=mask)
+    torch.cuda.synchronize()
+    assert bits_equal(W, want_w), first_mismatch(W, want_w)
+    assert np.array_equal(mask.cpu().numpy(), want_mask)
+    if pad:
+        base = W._base if W._base is not None else W
+        assert torch.all(base[:, cols:] == 7.0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("axes", AXES)
+@pytest.mark.parametrize("ties", [False, True])
+def test_unstructured_half(gpu_device, dtype, axes, ties):
+    # line lengths that are not multiples of the block's stride; several column slabs
+    rows, cols = 331, 8 * 37
+    length = rows if axes[1] == "rows" else cols
+    alpha = 0.5 if axes[0] == axes[1] else 1.0
+    _run_case(gpu_device, rows, cols, dtype, axes, alpha, length // 2, seed=3, ties=ties)
+
+
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+def test_unstructured_quota_edges(gpu_device, axes):
+    rows, cols = 70, 72
+    length = rows if axes[1] == "rows" else cols
+    for n_prune in (0, 1, length - 1, length):
+        for ties in (False, True):
+            _run_case(gpu_device, rows, cols, torch.bfloat16, axes, 0.5, n_prune, seed=4, ties=ties)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_unstructured_magnitude_ties_on_long_lines(gpu_device, dtype):
+    """alpha = 0 on bf16-grid weights: thousands of exact ties per line, index rule decides."""
+    _run_case(gpu_device, 24, 4096, dtype, ("cols", "cols"), 0.0, 2048, seed=5, ties=True)
+    _run_case(gpu_device, 4096, 40, dtype, ("rows", "rows"), 0.0, 2048, seed=6, ties=True)
+    # a constant matrix: every position tied, lower indices survive
+    W = torch.full((300, 64), 0.5, dtype=dtype, device=gpu_device)
+    nrm = torch.ones(300, device=gpu_device)
+    want, _ = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), "rows", "rows", 1.0, 123)
+    dass.score_mask_unstructured(W, nrm, "rows", "rows", 1.0, 123)
+    torch.cuda.synchronize()
+    assert bits_equal(W, want), first_mismatch(W, want)
+
+
+def test_unstructured_leading_dimension(gpu_device):
+    _run_case(gpu_device, 100, 104, torch.bfloat16, ("cols", "cols"), 1.0, 52, seed=7, pad=24)
+    _run_case(gpu_device, 100, 104, torch.float32, ("rows", "rows"), 0.5, 50, seed=8, pad=12)
+
+
+def test_unstructured_mistral_shaped_lines(gpu_device):
+    """A few full-length comparison groups of the Mistral-7B-shaped config: Down rows of 14336
+    (7168 pruned), Gate columns of 14336 (stride d)."""
+    I, s = 14336, 0.5
+    g = torch.Generator(device="cpu").manual_seed(9)
+    nrm = synth.make_norms(I, "cpu", 9).to(gpu_device)
+    Wd = (torch.randn((6, I), generator=g) * 0.02).to(torch.bfloat16).to(gpu_device)
+    want, _ = oracle.mask_unstructured(to_np32(Wd), nrm.cpu().numpy(), "cols", "cols", 1.0, int(s * I))
+    dass.score_mask_unstructured(Wd, nrm, "cols", "cols", 1.0, int(s * I))
+    Wg = (torch.randn((I, 72), generator=g) * 0.02).to(torch.bfloat16).to(gpu_device)
+    want_g, _ = oracle.mask_unstructured(to_np32(Wg), nrm.cpu().numpy(), "rows", "rows", 0.5, int(s * I))
+    dass.score_mask_unstructured(Wg, nrm, "rows", "rows", 0.5, int(s * I))
+    torch.cuda.synchronize()
+    assert bits_equal(Wd, want), first_mismatch(Wd, want)
+    assert bits_equal(Wg, want_g), first_mismatch(Wg, want_g)
+
+
+def test_unstructured_argument_errors(gpu_device):
+    W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
+    nrm = torch.ones(16, device=gpu_device)
+    for bad in (-1, 17):
+        with pytest.raises(dass.DassError) as e:
+            dass.score_mask_unstructured(W, nrm, "cols", "cols", 1.0, bad)
+        assert e.value.status_name == "DASS_ERR_ARG"
+    torch.cuda.synchronize()
+    assert torch.all(W == 1)

@@ -1,0 +1,99 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before touching the GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_01943_amd as dass
+from paper_2405_01943_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return dass.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "dass.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dass_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert dass.version() >= 100
+    names = [lib.dass_status_string(i).decode() for i in range(8)]
+    assert names[0] == "DASS_OK" and len(set(names)) == 8
+    assert lib.dass_status_string(99) == b"DASS_ERR_UNKNOWN"
+
+
+def test_workspace_queries(lib):
+    assert lib.dass_calib_workspace_bytes(262144, 4096, 11008, 1) == 0
+    assert lib.dass_nm_workspace_bytes(11008, 4096, 0) >= 4 * 11008
+    assert lib.dass_nm_workspace_bytes(4096, 11008, 1) >= 4 * 11008
+    assert lib.dass_unstructured_workspace_bytes(4096, 14336, 1, 1, 1) >= 4 * 14336
+
+
+FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: every call below is rejected first
+ODD = ctypes.c_void_p(0x1004)
+
+
+def _nm(lib, W=FAKE, rows=64, cols=64, ld=64, dt=1, norms=FAKE, na=1, ga=1, alpha=1.0, n=2, m=4,
+        ws=FAKE, wsb=4096):
+    return lib.dass_status_string(lib.dass_score_mask_nm(W, rows, cols, ld, dt, norms, na, ga, alpha,
+                                                         n, m, None, ws, wsb, None)).decode()
+
+
+def test_nm_rejections(lib):
+    assert _nm(lib, W=None) == "DASS_ERR_NULL"
+    assert _nm(lib, norms=None) == "DASS_ERR_NULL"
+    assert _nm(lib, dt=5) == "DASS_ERR_DTYPE"
+    assert _nm(lib, rows=0) == "DASS_ERR_SHAPE"
+    assert _nm(lib, ld=56) == "DASS_ERR_SHAPE"
+    assert _nm(lib, cols=60, ld=64) == "DASS_ERR_SHAPE"          # cols % 8
+    assert _nm(lib, rows=6, na=0, ga=0) == "DASS_ERR_SHAPE"      # 6 rows, groups of 4
+    assert _nm(lib, m=3) == "DASS_ERR_ARG"
+    assert _nm(lib, n=4, m=4) == "DASS_ERR_ARG"
+    assert _nm(lib, n=0) == "DASS_ERR_ARG"
+    assert _nm(lib, alpha=-0.5) == "DASS_ERR_ARG"
+    assert _nm(lib, alpha=float("nan")) == "DASS_ERR_ARG"
+    assert _nm(lib, na=2) == "DASS_ERR_ARG"
+    assert _nm(lib, W=ODD) == "DASS_ERR_ALIGN"
+    assert _nm(lib, ld=68) == "DASS_ERR_ALIGN"                   # bf16 stride % 8
+    assert _nm(lib, ws=None) == "DASS_ERR_WORKSPACE"
+    assert _nm(lib, wsb=8) == "DASS_ERR_WORKSPACE"
+    assert "workspace" in lib.dass_last_error_string().decode()
+
+
+def test_unstructured_rejections(lib):
+    def call(n_prune=8, cols=64, ws=FAKE, wsb=4096, W=FAKE):
+        rc = lib.dass_score_mask_unstructured(W, 64, cols, 64, 1, FAKE, 1, 1, 1.0, n_prune, None,
+                                              ws, wsb, None)
+        return lib.dass_status_string(rc).decode()
+    assert call(n_prune=-1) == "DASS_ERR_ARG"
+    assert call(n_prune=65) == "DASS_ERR_ARG"
+    assert call(ws=None) == "DASS_ERR_WORKSPACE"
+    assert call(W=None) == "DASS_ERR_NULL"
+    assert call(cols=12) == "DASS_ERR_SHAPE"
+
+
+def test_calib_rejections(lib):
+    def call(X=FAKE, T=16, ldx=64, d=64, d_int=8, dt=1, act=0, sumsq=FAKE, ldw=64):
+        rc = lib.dass_calib_norms(X, T, ldx, FAKE, FAKE, ldw, d, d_int, dt, act, sumsq, 0, None,
+                                  None, 0, None)
+        return lib.dass_status_string(rc).decode()
+    assert call(X=None) == "DASS_ERR_NULL"
+    assert call(sumsq=None) == "DASS_ERR_NULL"
+    assert call(dt=2) == "DASS_ERR_DTYPE"
+    assert call(act=4) == "DASS_ERR_DTYPE"
+    assert call(T=0) == "DASS_ERR_SHAPE"
+    assert call(d=60, ldx=64) == "DASS_ERR_SHAPE"                # bf16 needs d % 8
+    assert call(ldx=32) == "DASS_ERR_SHAPE"
+    assert call(X=ODD) == "DASS_ERR_ALIGN"
+    assert call(ldw=68) == "DASS_ERR_ALIGN"
