@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the DaSS hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic calibration
+batch, inputs resident in HBM:
+  stage 1  dass_calib_norms over all calibration tokens (chunked if the config
+           says so), giving the f32 activation norms;
+  stage 2  dass_score_mask_nm on fresh copies of Gate, Up (alpha 0.5, groups down
+           the rows) and Down (alpha 1, groups along the rows), pruned in place.
+
+Prints ONE JSON line.  `value` is calibration tokens per second of the whole
+step.  `roofline` is for the dominant kernel (the stage-1 MFMA kernel);
+`roofline_stage2` is the N:M kernel timed launch by launch on copies that rotate
+through more memory than the 256 MB last-level cache.  `cpu_baseline` times the
+float64 oracle on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="llama2_7b")
+    ap.add_argument("--tokens", type=int, default=0, help="override the token count (debugging)")
+    ap.add_argument("--nm", default="2:4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage2-launches", type=int, default=24)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X_sample, norms32):
+    """Time the oracle as it stands: stage 1 on a token slice x all neurons, stage 2 on the three
+    full matrices; scale stage 1 linearly to the config's token count."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    f32 = lambda t: t.cpu().to(torch.float32).numpy()
+    xs, wg, wu, wd = f32(X_sample), f32(Wg), f32(Wu), f32(Wd)
+    t0 = time.perf_counter()
+    oracle.sumsq(xs, wg, wu, cfg.act)
+    t1 = time.perf_counter() - t0
+    s1_rate = xs.shape[0] / t1
+    t0 = time.perf_counter()
+    oracle.mask_nm(wg, norms32, "rows", "rows", cfg.alpha_gate_up, n_keep, m)
+    oracle.mask_nm(wu, norms32, "rows", "rows", cfg.alpha_gate_up, n_keep, m)
+    oracle.mask_nm(wd, norms32, "cols", "cols", cfg.alpha_down, n_keep, m)
+    t2 = time.perf_counter() - t0
+    step_s = cfg.tokens / s1_rate + t2
+    return {
+        "value": cfg.tokens / step_s, "unit": "tokens/s", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": (f"stage 1: all {cfg.d_int} neurons x first {xs.shape[0]} tokens in {t1:.1f} s "
+                   f"(scaled linearly to {cfg.tokens} tokens); stage 2: the three full matrices "
+                   f"in {t2:.2f} s"),
+        "stage1_tokens_per_s": s1_rate,
+        "stage2_GBps": 3 * 2 * Wg.numel() * Wg.element_size() / t2 / 1e9,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2405_01943_amd as dass
+    from paper_2405_01943_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dass.load_library()  # raises if the HIP library is missing
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    if args.tokens:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, tokens=args.tokens, chunk=min(cfg.chunk, args.tokens))
+    n_keep, m = (int(v) for v in args.nm.split(":"))
+    T, d, I = cfg.tokens, cfg.d, cfg.d_int
+    esz = 2 if cfg.dtype == "bf16" else 4
+
+    # ---- synthetic inputs, generated on the device chunk by chunk ----------------------
+    gen_chunk = min(T, 32768)
+    X = torch.empty((T, d), dtype=cfg.torch_dtype, device=dev)
+    for c in range((T + gen_chunk - 1) // gen_chunk):
+        lo = c * gen_chunk
+        n = min(gen_chunk, T - lo)
+        X[lo:lo + n] = synth.make_x(cfg, c, n, dev)
+    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
+    Wg_p, Wu_p, Wd_p = (torch.empty_like(w) for w in (Wg, Wu, Wd))
+    sumsq = torch.empty(I, device=dev)
+    norms = torch.empty(I, device=dev)
+    ws_gate = torch.empty(dass.nm_workspace_bytes(I, d, "rows"), dtype=torch.uint8, device=dev)
+    ws_down = torch.empty(dass.nm_workspace_bytes(d, I, "cols"), dtype=torch.uint8, device=dev)
+    chunks = [(lo, min(cfg.chunk, T - lo)) for lo in range(0, T, cfg.chunk)]
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    s1_ms, s2_ms = [], []
+
+    def step(record: bool):
+        Wg_p.copy_(Wg); Wu_p.copy_(Wu); Wd_p.copy_(Wd)
+        e = [ev() for _ in range(3)]
+        e[0].record()
+        for k, (lo, n) in enumerate(chunks):
+            dass.calib_norms(X[lo:lo + n], Wg, Wu, cfg.act, sumsq, accumulate=k > 0,
+                             norms_out=norms if k == len(chunks) - 1 else None)
+        e[1].record()
+        dass.score_mask_nm(Wg_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
+        dass.score_mask_nm(Wu_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
+        dass.score_mask_nm(Wd_p, norms, "cols", "cols", cfg.alpha_down, n_keep, m, workspace=ws_down)
+        e[2].record()
+        if record:
+            return e
+        return None
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = [step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for e in evs:
+        s1_ms.append(e[0].elapsed_time(e[1]))
+        s2_ms.append(e[1].elapsed_time(e[2]))
+    ms_per_step = wall * 1e3 / args.steps
+    s1_avg = sum(s1_ms) / len(s1_ms)
+    s2_avg = sum(s2_ms) / len(s2_ms)
+    flops = 4.0 * T * d * I
+    s1_tflops = flops / (s1_avg * 1e-3) / 1e12
+
+    # ---- stage 2, launch by launch, on copies rotating through > 256 MB ------------------
+    n_copies = max(2, int(320e6 // (Wd.numel() * esz)) + 1)
+    cold = {}
+    for name, W0, axes, alpha, ws in (("gate", Wg, ("rows", "rows"), cfg.alpha_gate_up, ws_gate),
+                                      ("down", Wd, ("cols", "cols"), cfg.alpha_down, ws_down)):
+        copies = [W0.clone() for _ in range(n_copies)]
+        times = []
+        for it in range(args.stage2_launches + 4):
+            w = copies[it % n_copies]
+            w.copy_(W0)
+            # touch the other copies so this one has left the caches before it is timed
+            for other in copies:
+                if other is not w:
+                    other.add_(0)
+            a, b = ev(), ev()
+            a.record()
+            dass.score_mask_nm(w, norms, axes[0], axes[1], alpha, n_keep, m, workspace=ws)
+            b.record()
+            torch.cuda.synchronize()
+            if it >= 4:
+                times.append(a.elapsed_time(b))
+        del copies
+        cold[name] = {"median_us": statistics.median(times) * 1e3, "min_us": min(times) * 1e3}
+    bytes_per_matrix = 2.0 * Wd.numel() * esz
+    s2_call_us = (2 * cold["gate"]["median_us"] + cold["down"]["median_us"]) / 3.0
+    s2_gbs = bytes_per_matrix / (s2_call_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "calib tokens/s (fused GLU-norm, %MFMA peak) + N:M mask GB/s, LLaMA2-7B MLP",
+        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}-shaped {cfg.act} MLP, one pass of calibration norms + "
+                               f"{n_keep}:{m} DaSS masks of gate/up/down",
+                   "d": d, "d_int": I, "tokens": T, "chunk": cfg.chunk, "nm": f"{n_keep}:{m}",
+                   "alpha_gate_up": cfg.alpha_gate_up, "alpha_down": cfg.alpha_down},
+        "roofline": {"kernel": "calib_mfma_kernel", "bound": "mfma", "achieved": s1_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": s1_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+        "roofline_stage2": {"kernel": "nm_rows_kernel x2 + nm_cols_kernel (per call, factor kernel "
+                                      "included)", "bound": "hbm", "achieved": s2_gbs,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": s2_gbs / PEAK_HBM_GBS,
+                            "traffic": None},
+        "stage1": {"ms": s1_avg, "tokens_per_s": T / (s1_avg * 1e-3), "TFLOPs": s1_tflops},
+        "stage2": {"in_step_ms_3_matrices": s2_avg, "cold_gate_us": cold["gate"],
+                   "cold_down_us": cold["down"], "copies_rotated": n_copies,
+                   "bytes_per_matrix": bytes_per_matrix},
+    }
+    if not args.no_cpu_baseline:
+        n_sample = min(T, 2048)
+        out["cpu_baseline"] = cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X[:n_sample],
+                                           norms.cpu().numpy())
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
