@@ -21,9 +21,7 @@ namespace dass {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-struct alignas(16) Chunk {
-    uint32_t w[4];
-};
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // one 16-byte chunk = 8 bf16
 
 // ------------------------------------------------------------- activations --
 template <int ACT>
@@ -74,17 +72,19 @@ __global__ void sqrt_kernel(const float *__restrict__ sumsq, float *__restrict__
 }
 
 // ------------------------------------------------------------------ bf16 MFMA --
-// Position (in 16-byte chunks) of chunk c of tile row r inside the row's BK/8
-// chunk slots.  Rows r and r+8 share a parity, so the extra bit keeps any 16
-// consecutive rows of one chunk column on distinct (row parity, slot) pairs.
+// Slot (in 16-byte units) of K-chunk c of tile row r inside the row's CHUNKS
+// slots.  A 16-byte fragment read is served for 16 lanes = 16 consecutive rows
+// at a time; 16 / CHUNKS rows share one 256-byte line of the 64 banks, so the
+// XOR term changes every 16 / CHUNKS rows and the 16 reads land on 16 distinct
+// (line half, slot) places.
 template <int CHUNKS>
 __device__ __forceinline__ int swizzle(int r, int c)
 {
-    return c ^ (((r & 7) ^ ((r >> 3) & 1)) & (CHUNKS - 1));
+    return c ^ ((r / (16 / CHUNKS)) & (CHUNKS - 1));
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int ACT>
-__global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
+template <int BM, int BN, int BK, int WM, int WN, int MINB, int ACT>
+__global__ __launch_bounds__(64 * WM * WN, MINB) void calib_mfma_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
     const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
     float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n)
@@ -150,19 +150,31 @@ __global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
         g_ptr[p] = Wg + r * ldw + ld_c * 8;
         u_ptr[p] = Wu + r * ldw + ld_c * 8;
     }
-    Chunk a_st[A_CHUNKS], g_st[B_CHUNKS], u_st[B_CHUNKS];
+    u32x4 a_st[A_CHUNKS], g_st[B_CHUNKS], u_st[B_CHUNKS];
 
     auto load_slab = [&](int64_t k0) {
-        // the K tail (d not a multiple of BK) is filled with zeros
-        const bool k_ok = k0 + ld_c * 8 < d;
-        const Chunk zero = {{0u, 0u, 0u, 0u}};
 #pragma unroll
         for (int p = 0; p < A_CHUNKS; ++p)
-            a_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(a_ptr[p] + k0) : zero;
+            a_st[p] = *reinterpret_cast<const u32x4 *>(a_ptr[p] + k0);
 #pragma unroll
         for (int p = 0; p < B_CHUNKS; ++p) {
-            g_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(g_ptr[p] + k0) : zero;
-            u_st[p] = k_ok ? *reinterpret_cast<const Chunk *>(u_ptr[p] + k0) : zero;
+            g_st[p] = *reinterpret_cast<const u32x4 *>(g_ptr[p] + k0);
+            u_st[p] = *reinterpret_cast<const u32x4 *>(u_ptr[p] + k0);
+        }
+    };
+    // Last slab when d is not a multiple of BK: chunks past d are read from the
+    // row's first chunk instead (always in range) and cleared.
+    auto load_slab_tail = [&](int64_t k0) {
+        const bool k_ok = k0 + ld_c * 8 < d;
+        const int64_t off = k_ok ? k0 : -(int64_t)(ld_c * 8);
+        const uint32_t keep = k_ok ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int p = 0; p < A_CHUNKS; ++p)
+            a_st[p] = *reinterpret_cast<const u32x4 *>(a_ptr[p] + off) & keep;
+#pragma unroll
+        for (int p = 0; p < B_CHUNKS; ++p) {
+            g_st[p] = *reinterpret_cast<const u32x4 *>(g_ptr[p] + off) & keep;
+            u_st[p] = *reinterpret_cast<const u32x4 *>(u_ptr[p] + off) & keep;
         }
     };
     auto store_slab = [&](int buf) {
@@ -170,14 +182,14 @@ __global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
 #pragma unroll
         for (int p = 0; p < A_CHUNKS; ++p) {
             const int r = ld_r + p * ROWS_PER_PASS;
-            *reinterpret_cast<Chunk *>(base + (r * CH + swizzle<CH>(r, ld_c)) * 16) = a_st[p];
+            *reinterpret_cast<u32x4 *>(base + (r * CH + swizzle<CH>(r, ld_c)) * 16) = a_st[p];
         }
 #pragma unroll
         for (int p = 0; p < B_CHUNKS; ++p) {
             const int r = ld_r + p * ROWS_PER_PASS;
             const int off = (r * CH + swizzle<CH>(r, ld_c)) * 16;
-            *reinterpret_cast<Chunk *>(base + A_BYTES + off) = g_st[p];
-            *reinterpret_cast<Chunk *>(base + A_BYTES + B_BYTES + off) = u_st[p];
+            *reinterpret_cast<u32x4 *>(base + A_BYTES + off) = g_st[p];
+            *reinterpret_cast<u32x4 *>(base + A_BYTES + B_BYTES + off) = u_st[p];
         }
     };
 
@@ -197,7 +209,14 @@ __global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
     const int fr = lane & 31, fc = lane >> 5;
 
     const int64_t n_slabs = (d + BK - 1) / BK;
-    load_slab(0);
+    const bool ragged_k = d % BK != 0;
+    auto fetch = [&](int64_t slab) {
+        if (ragged_k && slab == n_slabs - 1)
+            load_slab_tail(slab * BK);
+        else
+            load_slab(slab * BK);
+    };
+    fetch(0);
     store_slab(0);
     __syncthreads();
 
@@ -205,7 +224,7 @@ __global__ __launch_bounds__(64 * WM * WN) void calib_mfma_kernel(
         const int cur = (int)(ks & 1);
         const bool more = ks + 1 < n_slabs;
         if (more)
-            load_slab((ks + 1) * BK);
+            fetch(ks + 1);
 
         const char *base = lds + cur * STAGE;
 #pragma unroll
@@ -342,7 +361,7 @@ __global__ __launch_bounds__(256) void calib_f32_kernel(
 }
 
 // ------------------------------------------------------------------ host side --
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int MINB>
 static void launch_mfma(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T,
                         int64_t ldx, const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d,
                         int64_t d_int, float *sumsq, int64_t tiles_t, int64_t tiles_n)
@@ -350,19 +369,19 @@ static void launch_mfma(int act, dim3 grid, hipStream_t stream, const uint16_t *
     const dim3 block(64 * WM * WN);
     switch (act) {
     case DASS_ACT_SILU:
-        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_SILU>), grid, block, 0,
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, MINB, DASS_ACT_SILU>), grid, block, 0,
                            stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
         break;
     case DASS_ACT_GELU_TANH:
-        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_GELU_TANH>), grid, block,
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, MINB, DASS_ACT_GELU_TANH>), grid, block,
                            0, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
         break;
     case DASS_ACT_GELU_ERF:
-        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_GELU_ERF>), grid, block,
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, MINB, DASS_ACT_GELU_ERF>), grid, block,
                            0, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
         break;
     default:
-        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, DASS_ACT_RELU>), grid, block, 0,
+        hipLaunchKernelGGL((calib_mfma_kernel<BM, BN, BK, WM, WN, MINB, DASS_ACT_RELU>), grid, block, 0,
                            stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n);
         break;
     }
@@ -423,7 +442,7 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         const int64_t blocks = (n_tiles + 7) / 8 * 8;
         if (blocks > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
-        launch_mfma<BM, BN, BK, 2, 2>((int)act, dim3((unsigned)blocks), stream,
+        launch_mfma<BM, BN, BK, 4, 2, 1>((int)act, dim3((unsigned)blocks), stream,
                                       static_cast<const uint16_t *>(X), T, ldx,
                                       static_cast<const uint16_t *>(Wgate),
                                       static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
