@@ -187,7 +187,7 @@ def main():
                                f"{n_keep}:{m} DaSS masks of gate/up/down",
                    "d": d, "d_int": I, "tokens": T, "chunk": cfg.chunk, "nm": f"{n_keep}:{m}",
                    "alpha_gate_up": cfg.alpha_gate_up, "alpha_down": cfg.alpha_down},
-        "roofline": {"kernel": "calib_mfma_kernel", "bound": "mfma", "achieved": s1_tflops,
+        "roofline": {"kernel": "calib_pipe_kernel", "bound": "mfma", "achieved": s1_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": s1_tflops / PEAK_BF16_TFLOPS,
                      "traffic": None},
         "roofline_stage2": {"kernel": "nm_rows_kernel x2 + nm_cols_kernel (per call, factor kernel "
