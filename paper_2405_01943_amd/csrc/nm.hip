@@ -3,7 +3,17 @@
 // "Extension to N:M Sparsity"), write +0 over the rest in place.
 //
 // One streaming pass: every weight is read once and written once with 16-byte
-// accesses; selection happens in registers on the exact f64 product.
+// accesses; selection happens in registers on exact scores.
+//
+// Two families of kernels:
+//   nm_half_*   the patterns the paper uses, n_keep = m / 2 for m = 2, 4, 8, with
+//               alpha in {0, 0.5, 1}: the factor is computed in the kernel, scores
+//               are exact two-term f32 sums compared a wavefront at a time, the
+//               selection is scalar mask logic, accesses are non-temporal and every
+//               thread makes a single pass (many small workgroups keep HBM busier
+//               than a resident grid that loops).
+//   nm_*        every other (n_keep, m, alpha): factor vector from a helper kernel,
+//               scores as f64 products, selection by counting wins per lane.
 #include "select.h"
 
 #include <mutex>
@@ -11,6 +21,320 @@
 namespace dass {
 
 constexpr int kBlock = 256;
+
+// ---------------------------------------------------------------------------
+// n_keep = m / 2, factor computed in the kernel
+// ---------------------------------------------------------------------------
+enum { kFactorOne = 0, kFactorNorm = 1, kFactorSqrt = 2 };
+
+// f = norm^alpha for alpha = 0, 1, 0.5.  sqrtf is the correctly rounded f32 square
+// root (this file is built without fast-math), which equals the f64 square root
+// rounded to f32.
+__device__ __forceinline__ float factor_of(float norm, int fmode)
+{
+    if (fmode == kFactorSqrt)
+        return sqrtf(norm);
+    return fmode == kFactorNorm ? norm : 1.0f;
+}
+
+// Below this product the rounding error of p may not be an f32; at or above
+// kHugeScore p may have overflowed.  Either sends the wavefront to the f64 path.
+constexpr float kTinyScore = 0x1p-100f, kHugeScore = 0x1p+127f;
+
+template <int DT>
+__device__ __forceinline__ float elem_of(const u32x4 &v, int e)   // element e of a 16-byte vector, as f32
+{
+    if constexpr (DT == DASS_BF16) {
+        const uint32_t w = v[e >> 1];
+        return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+    } else {
+        return __uint_as_float(v[e]);
+    }
+}
+
+// Element e of v becomes +0 in the lanes where `keep` is clear.
+template <int DT>
+__device__ __forceinline__ void clear_unless(u32x4 &v, int e, lanemask_t keep)
+{
+    const bool k = __builtin_amdgcn_inverse_ballot_w64(keep);
+    if constexpr (DT == DASS_BF16) {
+        const uint32_t w = v[e >> 1];
+        v[e >> 1] = k ? w : (w & ((e & 1) ? 0x0000ffffu : 0xffff0000u));
+    } else {
+        v[e] = k ? v[e] : 0u;
+    }
+}
+
+// |W[r, c]| straight from memory, and W[r, c] = +0: the element-wise accesses of the rare exact path.
+template <int DT>
+__device__ __forceinline__ float abs_at(const char *W, int64_t r, int64_t c, int64_t ld)
+{
+    if constexpr (DT == DASS_BF16)
+        return __uint_as_float(((uint32_t) * reinterpret_cast<const uint16_t *>(W + (r * ld + c) * 2) << 16) & 0x7fffffffu);
+    else
+        return __uint_as_float(*reinterpret_cast<const uint32_t *>(W + (r * ld + c) * 4) & 0x7fffffffu);
+}
+template <int DT>
+__device__ __forceinline__ void zero_at(char *W, int64_t r, int64_t c, int64_t ld)
+{
+    if constexpr (DT == DASS_BF16)
+        *reinterpret_cast<uint16_t *>(W + (r * ld + c) * 2) = 0;
+    else
+        *reinterpret_cast<uint32_t *>(W + (r * ld + c) * 4) = 0u;
+}
+
+// Is the two-term f32 form of the score |w| * f exact?  Not when the product is so small that
+// its rounding error underflows (unless it is an exact zero), nor when it overflows.
+__device__ __forceinline__ bool score_needs_f64(float w, float f)
+{
+    const float p = w * f;
+    return (p < kTinyScore && w != 0.0f && f != 0.0f) || !(p < kHugeScore);
+}
+
+// Groups run down a column (stride ld): Gate-Proj and Up-Proj.  A thread owns the EPV
+// columns of one 16-byte vector and GB groups of M rows; a workgroup covers 256 such
+// column slots, so every row is read and written in contiguous 4 KB pieces.
+template <int DT, int M, bool NORM_ROWS, bool WITH_MASK>
+__global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
+    void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
+    int fmode, uint8_t *__restrict__ mask, int64_t nbx)
+{
+    constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
+    constexpr int GB = M >= 4 ? 1 : 2;
+    constexpr int EB = DT == DASS_BF16 ? 2 : 4;
+
+    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
+    const int64_t slot = bx * kBlock + threadIdx.x;
+    // Lanes past the last column slot stay in the kernel (the mask-byte exchange at the end
+    // needs every lane): they read column 0 and write nothing.
+    const bool active = slot < cols / EPV;
+    const int64_t c0 = (active ? slot : 0) * EPV;
+    const int64_t n_groups = rows / M;
+    char *W = static_cast<char *>(Wv);
+
+    float fc[EPV];
+    if constexpr (!NORM_ROWS) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e)
+            fc[e] = factor_of(norms[c0 + e], fmode);
+    }
+
+    u32x4 v[GB][M];
+    float fr[GB][M];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        const int64_t r0 = (by * GB + g) * M;
+        if (by * GB + g < n_groups) {
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                v[g][a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
+                if constexpr (NORM_ROWS)
+                    fr[g][a] = factor_of(norms[r0 + a], fmode);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        if (by * GB + g >= n_groups)
+            break;
+        const int64_t r0 = (by * GB + g) * M;
+        // Optimistic pass on the two-term scores, applied to the registers straight away.
+        float pmin = kHugeScore, pmax = 0.0f;
+        uint32_t kept[M];
+#pragma unroll
+        for (int a = 0; a < M; ++a)
+            kept[a] = 0;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            float p[M], q[M];
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[g][a] : fc[e];
+                p[a] = w * f;
+                q[a] = fmaf(w, f, -p[a]);
+                pmin = fminf(pmin, p[a]);
+                pmax = fmaxf(pmax, p[a]);
+            }
+            keep_top_half<M>(p, q, [&](int a, lanemask_t keep) {
+                clear_unless<DT>(v[g][a], e, keep);
+                if constexpr (WITH_MASK)
+                    kept[a] |= __builtin_amdgcn_inverse_ballot_w64(keep) ? (1u << e) : 0u;
+            });
+            // one column at a time: interleaving the lane masks of several overflows the scalar registers
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // Any score outside the range where the two-term sum is exact?  (A zero score is fine
+        // when the weight or the factor is exactly zero; the second look sorts that out.)  Then
+        // the whole wavefront redoes its groups element by element on the weights still in
+        // memory, with f64 products, which are exact over the whole f32 range, and writes the
+        // zeros itself.
+        bool exact_path = false;
+        if (__builtin_amdgcn_fcmpf(pmin, kTinyScore, kCmpLt) | ~__builtin_amdgcn_fcmpf(pmax, kHugeScore, kCmpLt)) {
+            bool risky = false;
+#pragma unroll 1
+            for (int e = 0; e < EPV; ++e)
+#pragma unroll
+                for (int a = 0; a < M; ++a)
+                    risky |= score_needs_f64(abs_at<DT>(W, r0 + a, c0 + e, ld),
+                                             NORM_ROWS ? fr[g][a] : factor_of(norms[c0 + e], fmode));
+            exact_path = __builtin_amdgcn_ballot_w64(risky) != 0;
+        }
+        if (exact_path) {
+#pragma unroll
+            for (int a = 0; a < M; ++a)
+                kept[a] = 0;
+#pragma unroll 1
+            for (int e = 0; e < EPV; ++e) {
+                double sc[M];
+#pragma unroll
+                for (int a = 0; a < M; ++a)
+                    sc[a] = (double)abs_at<DT>(W, r0 + a, c0 + e, ld) *
+                            (double)(NORM_ROWS ? fr[g][a] : factor_of(norms[c0 + e], fmode));
+                const uint32_t bits = nm_keep_bits<M>(sc, M / 2);
+#pragma unroll
+                for (int a = 0; a < M; ++a) {
+                    if (active && !((bits >> a) & 1u))
+                        zero_at<DT>(W, r0 + a, c0 + e, ld);
+                    kept[a] |= ((bits >> a) & 1u) << e;
+                }
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+            if (active && !exact_path)
+                __builtin_nontemporal_store(v[g][a], reinterpret_cast<u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
+            if constexpr (WITH_MASK) {
+                if constexpr (EPV == 8) {
+                    if (active)
+                        mask[(r0 + a) * (cols / 8) + slot] = (uint8_t)kept[a];
+                } else {
+                    const uint32_t other = __shfl_xor(kept[a], 1, 64);
+                    if (active && (slot & 1) == 0)
+                        mask[(r0 + a) * (cols / 8) + slot / 2] = (uint8_t)(kept[a] | (other << 4));
+                }
+            }
+        }
+    }
+}
+
+// Groups run along a row (contiguous): Down-Proj.  A thread owns the UW = max(EPV, M)
+// consecutive columns of NV 16-byte vectors and RB rows; the factors of its columns are
+// computed once.
+template <int DT, int M, bool NORM_COLS, bool WITH_MASK>
+__global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
+    void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
+    int fmode, uint8_t *__restrict__ mask, int64_t nbx)
+{
+    constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
+    constexpr int UW = M > EPV ? M : EPV;
+    constexpr int NV = UW / EPV;
+    constexpr int RB = NV == 1 ? 4 : 2;
+    constexpr int EB = DT == DASS_BF16 ? 2 : 4;
+
+    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
+    const int64_t slot = bx * kBlock + threadIdx.x;
+    const bool active = slot < cols / UW;
+    const int64_t c0 = (active ? slot : 0) * UW;
+    char *W = static_cast<char *>(Wv);
+
+    float fc[UW];
+    if constexpr (NORM_COLS) {
+#pragma unroll
+        for (int e = 0; e < UW; ++e)
+            fc[e] = factor_of(norms[c0 + e], fmode);
+    }
+
+    u32x4 v[RB][NV];
+    float fr[RB];
+#pragma unroll
+    for (int k = 0; k < RB; ++k) {
+        const int64_t r = by * RB + k;
+        if (r < rows) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j)
+                v[k][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
+            if constexpr (!NORM_COLS)
+                fr[k] = factor_of(norms[r], fmode);
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < RB; ++k) {
+        const int64_t r = by * RB + k;
+        if (r >= rows)
+            break;
+        float pmin = kHugeScore, pmax = 0.0f;
+        uint32_t kept = 0;
+#pragma unroll
+        for (int g = 0; g < UW / M; ++g) {
+            float p[M], q[M];
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const int e = g * M + a;
+                const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr[k];
+                p[a] = w * f;
+                q[a] = fmaf(w, f, -p[a]);
+                pmin = fminf(pmin, p[a]);
+                pmax = fmaxf(pmax, p[a]);
+            }
+            keep_top_half<M>(p, q, [&](int a, lanemask_t keep) {
+                const int e = g * M + a;
+                clear_unless<DT>(v[k][e / EPV], e % EPV, keep);
+                if constexpr (WITH_MASK)
+                    kept |= __builtin_amdgcn_inverse_ballot_w64(keep) ? (1u << e) : 0u;
+            });
+        }
+        // as in nm_half_rows_kernel: leave the fast path when a score is out of its exact range
+        bool exact_path = false;
+        if (__builtin_amdgcn_fcmpf(pmin, kTinyScore, kCmpLt) | ~__builtin_amdgcn_fcmpf(pmax, kHugeScore, kCmpLt)) {
+            bool risky = false;
+#pragma unroll 1
+            for (int e = 0; e < UW; ++e)
+                risky |= score_needs_f64(abs_at<DT>(W, r, c0 + e, ld),
+                                         NORM_COLS ? factor_of(norms[c0 + e], fmode) : fr[k]);
+            exact_path = __builtin_amdgcn_ballot_w64(risky) != 0;
+        }
+        if (exact_path) {
+            kept = 0;
+#pragma unroll 1
+            for (int g = 0; g < UW / M; ++g) {
+                double sc[M];
+#pragma unroll
+                for (int a = 0; a < M; ++a)
+                    sc[a] = (double)abs_at<DT>(W, r, c0 + g * M + a, ld) *
+                            (double)(NORM_COLS ? factor_of(norms[c0 + g * M + a], fmode) : fr[k]);
+                const uint32_t bits = nm_keep_bits<M>(sc, M / 2);
+#pragma unroll
+                for (int a = 0; a < M; ++a)
+                    if (active && !((bits >> a) & 1u))
+                        zero_at<DT>(W, r, c0 + g * M + a, ld);
+                kept |= bits << (g * M);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            if (active && !exact_path)
+                __builtin_nontemporal_store(v[k][j], reinterpret_cast<u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
+        if constexpr (WITH_MASK) {
+            if constexpr (UW >= 8) {
+                if (active) {
+#pragma unroll
+                    for (int b = 0; b < UW / 8; ++b)
+                        mask[r * (cols / 8) + c0 / 8 + b] = (uint8_t)(kept >> (8 * b));
+                }
+            } else {
+                const uint32_t other = __shfl_xor(kept, 1, 64);
+                if (active && (slot & 1) == 0)
+                    mask[r * (cols / 8) + slot / 2] = (uint8_t)(kept | (other << 4));
+            }
+        }
+    }
+}
+
+// ===========================================================================
+// General path: any (n_keep, m, alpha)
+// ===========================================================================
 
 // ---------------------------------------------------------------------------
 // Groups run along a row (contiguous in memory): Down-Proj.
@@ -249,6 +573,37 @@ static nm_kernel_t pick_kernel_m(int m, int group_axis, int norm_axis)
     return nullptr;
 }
 
+using nm_half_kernel_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint8_t *,
+                                  int64_t);
+
+template <int DT, int M, bool WITH_MASK>
+static nm_half_kernel_t pick_half_kernel(int group_axis, int norm_axis)
+{
+    if (group_axis == DASS_AXIS_COLS)
+        return norm_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK>
+                                           : nm_half_cols_kernel<DT, M, false, WITH_MASK>;
+    return norm_axis == DASS_AXIS_ROWS ? nm_half_rows_kernel<DT, M, true, WITH_MASK>
+                                       : nm_half_rows_kernel<DT, M, false, WITH_MASK>;
+}
+
+template <int DT, bool WITH_MASK>
+static nm_half_kernel_t pick_half_kernel_m(int m, int group_axis, int norm_axis)
+{
+    switch (m) {
+    case 2: return pick_half_kernel<DT, 2, WITH_MASK>(group_axis, norm_axis);
+    case 4: return pick_half_kernel<DT, 4, WITH_MASK>(group_axis, norm_axis);
+    case 8: return pick_half_kernel<DT, 8, WITH_MASK>(group_axis, norm_axis);
+    }
+    return nullptr;
+}
+
+template <int DT>
+static nm_half_kernel_t pick_half_kernel_mask(bool with_mask, int m, int group_axis, int norm_axis)
+{
+    return with_mask ? pick_half_kernel_m<DT, true>(m, group_axis, norm_axis)
+                     : pick_half_kernel_m<DT, false>(m, group_axis, norm_axis);
+}
+
 }  // namespace dass
 
 extern "C" size_t dass_nm_workspace_bytes(int64_t rows, int64_t cols, dass_axis norm_axis)
@@ -280,6 +635,32 @@ extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, i
                     (long long)len, m);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // The paper's patterns with an exponent whose factor has an exact f32 recipe: one kernel.
+    if (2 * n_keep == m && m <= 8 && (alpha == 0.0 || alpha == 0.5 || alpha == 1.0)) {
+        const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
+        const int epv = vec_elems(dt);
+        nm_half_kernel_t kernel =
+            dt == DASS_BF16 ? pick_half_kernel_mask<DASS_BF16>(mask_out != nullptr, m, group_axis, norm_axis)
+                            : pick_half_kernel_mask<DASS_F32>(mask_out != nullptr, m, group_axis, norm_axis);
+        int64_t slots, batches;   // one thread per (column slot, row batch), no loop
+        if (group_axis == DASS_AXIS_COLS) {
+            const int uw = m > epv ? m : epv;
+            slots = cols / uw;
+            batches = (rows + (uw == epv ? 4 : 2) - 1) / (uw == epv ? 4 : 2);
+        } else {
+            slots = cols / epv;
+            const int gb = m >= 4 ? 1 : 2;
+            batches = (rows / m + gb - 1) / gb;
+        }
+        const int64_t nbx = (slots + kBlock - 1) / kBlock;
+        if (nbx * batches > 0x7fffffffLL)
+            return fail(DASS_ERR_SHAPE, "%s: matrix too large for one launch", fn);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbx * batches)), dim3(kBlock), 0, stream, W, rows, cols, ld,
+                           norms, fmode, mask_out, nbx);
+        return check_launch("N:M kernel");
+    }
+
     float *f = static_cast<float *>(workspace);
     const int64_t n_norm = norm_axis == DASS_AXIS_ROWS ? rows : cols;
     st = launch_factor(norms, n_norm, alpha, f, stream);

@@ -89,6 +89,36 @@ def test_nm_smallest_shapes(gpu_device):
         _run_case(gpu_device, 16, 16, dtype, ("cols", "cols"), 1.0, 8, 16, seed=33)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+@pytest.mark.parametrize("n_keep,m", [(1, 2), (2, 4), (4, 8)])
+def test_nm_extreme_magnitudes(gpu_device, dtype, axes, n_keep, m):
+    """Scores near the bottom and the top of the f32 range (subnormal weights, tiny and huge norms,
+    products that underflow or overflow in f32) and exact zeros: the selection must stay exact."""
+    rows, cols = 64, 256
+    g = torch.Generator(device="cpu").manual_seed(77)
+    mant = torch.rand((rows, cols), generator=g) + 1.0
+    expo = torch.randint(-140, -100, (rows, cols), generator=g).to(torch.float32)
+    W = (mant * torch.exp2(expo)).to(dtype)                       # tiny, partly subnormal
+    W[::3] = (mant[::3] * torch.exp2(expo[::3] + 225.0)).to(dtype)  # huge
+    W[:, ::5] = 0.0
+    W = W * torch.where(torch.rand((rows, cols), generator=g) < 0.5, -1.0, 1.0).to(dtype)
+    n = rows if axes[0] == "rows" else cols
+    nrm = torch.exp2(torch.randint(-60, 60, (n,), generator=g).to(torch.float32)) * \
+        (torch.rand(n, generator=g) + 1.0)
+    nrm[::7] = 0.0
+    W, nrm = W.to(gpu_device), nrm.to(torch.float32).to(gpu_device)
+    for alpha in (0.5, 1.0):
+        Wc = W.clone()
+        want, want_mask = oracle.mask_nm(to_np32(Wc), nrm.cpu().numpy(), axes[0], axes[1], alpha, n_keep, m,
+                                         want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_nm(Wc, nrm, axes[0], axes[1], alpha, n_keep, m, mask_out=mask)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), first_mismatch(Wc, want)
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
 def test_nm_tiny_config_all_three_matrices(gpu_device):
     """Config 'tiny' (f32, d=256, d_int=688): Gate, Up with alpha 0.5 down rows; Down with alpha 1."""
     cfg = synth.CONFIGS["tiny"]
