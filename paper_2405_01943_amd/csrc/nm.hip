@@ -21,15 +21,15 @@
 namespace dass {
 
 constexpr int kBlock = 256;
+constexpr int kHalfColsRows = 4;   // 16-byte vectors per thread of nm_half_cols_kernel
 
 // ---------------------------------------------------------------------------
 // n_keep = m / 2, factor computed in the kernel
 // ---------------------------------------------------------------------------
 enum { kFactorOne = 0, kFactorNorm = 1, kFactorSqrt = 2 };
 
-// f = norm^alpha for alpha = 0, 1, 0.5.  sqrtf is the correctly rounded f32 square
-// root (this file is built without fast-math), which equals the f64 square root
-// rounded to f32.
+// f = norm^alpha for alpha = 0, 1, 0.5.  sqrtf is the correctly rounded f32 square root
+// (this file is built without fast-math), which equals the f64 square root rounded to f32.
 __device__ __forceinline__ float factor_of(float norm, int fmode)
 {
     if (fmode == kFactorSqrt)
@@ -37,9 +37,43 @@ __device__ __forceinline__ float factor_of(float norm, int fmode)
     return fmode == kFactorNorm ? norm : 1.0f;
 }
 
-// Below this product the rounding error of p may not be an f32; at or above
-// kHugeScore p may have overflowed.  Either sends the wavefront to the f64 path.
-constexpr float kTinyScore = 0x1p-100f, kHugeScore = 0x1p+127f;
+// N factors at once from the norms at src[0..N): all loads are issued before the first use,
+// and the exponent is tested once.  ok is cleared when a factor is outside the fast range;
+// the factors come back scaled by kFactorScale.  VEC: src is 16-byte aligned and differs from
+// lane to lane (16-byte loads); otherwise it is the same for the whole wavefront (scalar loads).
+template <int N, bool VEC>
+__device__ __forceinline__ void scaled_factors(const float *__restrict__ src, int fmode, float *f, bool &ok)
+{
+    float nrm[N];
+    if constexpr (VEC) {
+        static_assert(N % 4 == 0, "whole 16-byte vectors");
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            const u32x4 q = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                nrm[4 * i + k] = __uint_as_float(q[k]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            nrm[i] = src[i];
+    }
+    if (fmode == kFactorSqrt) {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            f[i] = sqrtf(nrm[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            f[i] = fmode == kFactorNorm ? nrm[i] : 1.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        ok &= factor_in_fast_range(f[i]);
+        f[i] *= kFactorScale;
+    }
+}
 
 template <int DT>
 __device__ __forceinline__ float elem_of(const u32x4 &v, int e)   // element e of a 16-byte vector, as f32
@@ -52,20 +86,7 @@ __device__ __forceinline__ float elem_of(const u32x4 &v, int e)   // element e o
     }
 }
 
-// Element e of v becomes +0 in the lanes where `keep` is clear.
-template <int DT>
-__device__ __forceinline__ void clear_unless(u32x4 &v, int e, lanemask_t keep)
-{
-    const bool k = __builtin_amdgcn_inverse_ballot_w64(keep);
-    if constexpr (DT == DASS_BF16) {
-        const uint32_t w = v[e >> 1];
-        v[e >> 1] = k ? w : (w & ((e & 1) ? 0x0000ffffu : 0xffff0000u));
-    } else {
-        v[e] = k ? v[e] : 0u;
-    }
-}
-
-// |W[r, c]| straight from memory, and W[r, c] = +0: the element-wise accesses of the rare exact path.
+// |W[r, c]| straight from memory, and W[r, c] = +0: the element-wise accesses of the rare f64 path.
 template <int DT>
 __device__ __forceinline__ float abs_at(const char *W, int64_t r, int64_t c, int64_t ld)
 {
@@ -83,135 +104,126 @@ __device__ __forceinline__ void zero_at(char *W, int64_t r, int64_t c, int64_t l
         *reinterpret_cast<uint32_t *>(W + (r * ld + c) * 4) = 0u;
 }
 
-// Is the two-term f32 form of the score |w| * f exact?  Not when the product is so small that
-// its rounding error underflows (unless it is an exact zero), nor when it overflows.
-__device__ __forceinline__ bool score_needs_f64(float w, float f)
-{
-    const float p = w * f;
-    return (p < kTinyScore && w != 0.0f && f != 0.0f) || !(p < kHugeScore);
-}
-
 // Groups run down a column (stride ld): Gate-Proj and Up-Proj.  A thread owns the EPV
-// columns of one 16-byte vector and GB groups of M rows; a workgroup covers 256 such
-// column slots, so every row is read and written in contiguous 4 KB pieces.
+// columns of one 16-byte vector and M rows (2 x M for M = 2): EPV (or 2 EPV) groups.  A
+// workgroup covers up to 256 such column slots, so rows are read and written in contiguous
+// pieces of up to 4 KB; every thread makes one pass and the grid covers the matrix (many small workgroups
+// keep HBM busier than a resident grid that loops).
 template <int DT, int M, bool NORM_ROWS, bool WITH_MASK>
 __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
-    int fmode, uint8_t *__restrict__ mask, int64_t nbx)
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
 {
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
-    constexpr int GB = M >= 4 ? 1 : 2;
+    constexpr int GB = M >= 4 ? 1 : 2;   // row groups per thread
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
 
-    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
-    const int64_t slot = bx * kBlock + threadIdx.x;
-    // Lanes past the last column slot stay in the kernel (the mask-byte exchange at the end
-    // needs every lane): they read column 0 and write nothing.
-    const bool active = slot < cols / EPV;
-    const int64_t c0 = (active ? slot : 0) * EPV;
+    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;   // 32-bit division
+    const int64_t slot = bx * blockDim.x + threadIdx.x;
+    // Lanes past the last column slot leave.  (With f32 two neighbouring lanes share a mask byte
+    // and exchange their halves at the end; cols is a multiple of 8, so they leave or stay together.)
+    if (slot >= cols / EPV)
+        return;
+    constexpr bool active = true;
+    const int64_t c0 = slot * EPV;
     const int64_t n_groups = rows / M;
     char *W = static_cast<char *>(Wv);
 
-    float fc[EPV];
-    if constexpr (!NORM_ROWS) {
-#pragma unroll
-        for (int e = 0; e < EPV; ++e)
-            fc[e] = factor_of(norms[c0 + e], fmode);
-    }
-
     u32x4 v[GB][M];
-    float fr[GB][M];
 #pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const int64_t r0 = (by * GB + g) * M;
+    for (int g = 0; g < GB; ++g)
         if (by * GB + g < n_groups) {
 #pragma unroll
-            for (int a = 0; a < M; ++a) {
-                v[g][a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
-                if constexpr (NORM_ROWS)
-                    fr[g][a] = factor_of(norms[r0 + a], fmode);
-            }
+            for (int a = 0; a < M; ++a)
+                v[g][a] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(W + (((by * GB + g) * M + a) * ld + c0) * EB));
         }
-    }
+
+    bool fast_ok = true;
+    float fc[EPV];   // scaled factors of the thread's columns, or ...
+    if constexpr (!NORM_ROWS)
+        scaled_factors<EPV, true>(norms + c0, fmode, fc, fast_ok);   // c0 is a multiple of 4: 16-byte loads
 
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
         if (by * GB + g >= n_groups)
             break;
         const int64_t r0 = (by * GB + g) * M;
-        // Optimistic pass on the two-term scores, applied to the registers straight away.
-        float pmin = kHugeScore, pmax = 0.0f;
-        uint32_t kept[M];
+        float fr[M];   // ... of the group's rows
+        if constexpr (NORM_ROWS)
+            scaled_factors<M, false>(norms + r0, fmode, fr, fast_ok);
+
+        // Outcomes of all pairs of rows, one bit per column (column e ends up in bit e).
+        PairWords<M> pw;
+        float pmax = 0.0f;
 #pragma unroll
-        for (int a = 0; a < M; ++a)
-            kept[a] = 0;
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) {
+        for (int e = EPV - 1; e >= 0; --e) {
             float p[M], q[M];
 #pragma unroll
             for (int a = 0; a < M; ++a) {
-                const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[g][a] : fc[e];
+                const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[a] : fc[e];
                 p[a] = w * f;
                 q[a] = fmaf(w, f, -p[a]);
-                pmin = fminf(pmin, p[a]);
                 pmax = fmaxf(pmax, p[a]);
             }
-            keep_top_half<M>(p, q, [&](int a, lanemask_t keep) {
-                clear_unless<DT>(v[g][a], e, keep);
-                if constexpr (WITH_MASK)
-                    kept[a] |= __builtin_amdgcn_inverse_ballot_w64(keep) ? (1u << e) : 0u;
-            });
-            // one column at a time: interleaving the lane masks of several overflows the scalar registers
-            __builtin_amdgcn_sched_barrier(0);
+            push_group<M>(pw, p, q);
+            __builtin_amdgcn_sched_barrier(0);   // one column at a time keeps the register count down
         }
-        // Any score outside the range where the two-term sum is exact?  (A zero score is fine
-        // when the weight or the factor is exactly zero; the second look sorts that out.)  Then
-        // the whole wavefront redoes its groups element by element on the weights still in
-        // memory, with f64 products, which are exact over the whole f32 range, and writes the
-        // zeros itself.
-        bool exact_path = false;
-        if (__builtin_amdgcn_fcmpf(pmin, kTinyScore, kCmpLt) | ~__builtin_amdgcn_fcmpf(pmax, kHugeScore, kCmpLt)) {
-            bool risky = false;
-#pragma unroll 1
-            for (int e = 0; e < EPV; ++e)
-#pragma unroll
-                for (int a = 0; a < M; ++a)
-                    risky |= score_needs_f64(abs_at<DT>(W, r0 + a, c0 + e, ld),
-                                             NORM_ROWS ? fr[g][a] : factor_of(norms[c0 + e], fmode));
-            exact_path = __builtin_amdgcn_ballot_w64(risky) != 0;
-        }
+        uint32_t keep[M];
+        keep_words<M>(pw, keep);
+
+        // A factor outside the fast range or a product that overflowed (in any lane): the
+        // whole wavefront redoes its groups element by element on the weights still in memory,
+        // with f64 products, which are exact over the whole f32 range, and writes the zeros itself.
+        const bool exact_path = __builtin_amdgcn_ballot_w64(!fast_ok || !(pmax < INFINITY)) != 0;
         if (exact_path) {
 #pragma unroll
             for (int a = 0; a < M; ++a)
-                kept[a] = 0;
+                keep[a] = 0;
 #pragma unroll 1
             for (int e = 0; e < EPV; ++e) {
                 double sc[M];
 #pragma unroll
                 for (int a = 0; a < M; ++a)
                     sc[a] = (double)abs_at<DT>(W, r0 + a, c0 + e, ld) *
-                            (double)(NORM_ROWS ? fr[g][a] : factor_of(norms[c0 + e], fmode));
+                            (double)factor_of(norms[NORM_ROWS ? r0 + a : c0 + e], fmode);
                 const uint32_t bits = nm_keep_bits<M>(sc, M / 2);
 #pragma unroll
                 for (int a = 0; a < M; ++a) {
                     if (active && !((bits >> a) & 1u))
                         zero_at<DT>(W, r0 + a, c0 + e, ld);
-                    kept[a] |= ((bits >> a) & 1u) << e;
+                    keep[a] |= ((bits >> a) & 1u) << e;
                 }
             }
-        }
+        } else {
 #pragma unroll
-        for (int a = 0; a < M; ++a) {
-            if (active && !exact_path)
-                __builtin_nontemporal_store(v[g][a], reinterpret_cast<u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
-            if constexpr (WITH_MASK) {
+            for (int a = 0; a < M; ++a) {
+                if constexpr (DT == DASS_BF16) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t lo = spread_bit(keep[a], 2 * j), hi = spread_bit(keep[a], 2 * j + 1);
+                        v[g][a][j] &= (lo & 0x0000ffffu) | (hi & 0xffff0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[g][a][j] &= spread_bit(keep[a], j);
+                }
+                if (active)
+                    __builtin_nontemporal_store(v[g][a], reinterpret_cast<u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
+            }
+        }
+        if constexpr (WITH_MASK) {
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const uint32_t kept = keep[a] & ((1u << EPV) - 1u);
                 if constexpr (EPV == 8) {
                     if (active)
-                        mask[(r0 + a) * (cols / 8) + slot] = (uint8_t)kept[a];
-                } else {
-                    const uint32_t other = __shfl_xor(kept[a], 1, 64);
+                        mask[(r0 + a) * (cols / 8) + slot] = (uint8_t)kept;
+                } else {   // two lanes share a byte: the even lane writes both halves
+                    const uint32_t other = __shfl_xor(kept, 1, 64);
                     if (active && (slot & 1) == 0)
-                        mask[(r0 + a) * (cols / 8) + slot / 2] = (uint8_t)(kept[a] | (other << 4));
+                        mask[(r0 + a) * (cols / 8) + slot / 2] = (uint8_t)(kept | (other << 4));
                 }
             }
         }
@@ -219,91 +231,89 @@ __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
 }
 
 // Groups run along a row (contiguous): Down-Proj.  A thread owns the UW = max(EPV, M)
-// consecutive columns of NV 16-byte vectors and RB rows; the factors of its columns are
-// computed once.
+// consecutive columns of NV 16-byte vectors and RB rows, RB * UW / M groups; the factors of
+// its columns are computed once.
 template <int DT, int M, bool NORM_COLS, bool WITH_MASK>
 __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
-    int fmode, uint8_t *__restrict__ mask, int64_t nbx)
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
 {
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int UW = M > EPV ? M : EPV;
     constexpr int NV = UW / EPV;
-    constexpr int RB = NV == 1 ? 4 : 2;
+    constexpr int RB = kHalfColsRows / NV;
+    constexpr int GPR = UW / M;   // groups per row
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
 
-    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
-    const int64_t slot = bx * kBlock + threadIdx.x;
+    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;   // 32-bit division
+    const int64_t slot = bx * blockDim.x + threadIdx.x;
+    // Lanes past the last column slot read column 0 and write nothing.  (Measured: letting them
+    // leave early instead makes this kernel slower.)
     const bool active = slot < cols / UW;
     const int64_t c0 = (active ? slot : 0) * UW;
     char *W = static_cast<char *>(Wv);
 
-    float fc[UW];
-    if constexpr (NORM_COLS) {
-#pragma unroll
-        for (int e = 0; e < UW; ++e)
-            fc[e] = factor_of(norms[c0 + e], fmode);
-    }
-
     u32x4 v[RB][NV];
-    float fr[RB];
 #pragma unroll
-    for (int k = 0; k < RB; ++k) {
-        const int64_t r = by * RB + k;
-        if (r < rows) {
+    for (int k = 0; k < RB; ++k)
+        if (by * RB + k < rows) {
 #pragma unroll
             for (int j = 0; j < NV; ++j)
-                v[k][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
-            if constexpr (!NORM_COLS)
-                fr[k] = factor_of(norms[r], fmode);
+                v[k][j] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(W + ((by * RB + k) * ld + c0) * EB + 16 * j));
         }
+
+    bool fast_ok = true;
+    float fc[UW];
+    if constexpr (NORM_COLS)
+        scaled_factors<UW, true>(norms + c0, fmode, fc, fast_ok);   // c0 is a multiple of 4: 16-byte loads
+    float frow[RB];
+    if constexpr (!NORM_COLS) {   // rows past the end (last batch only) reuse the last row's norm
+#pragma unroll
+        for (int k = 0; k < RB; ++k)
+            scaled_factors<1, false>(norms + (by * RB + k < rows ? by * RB + k : rows - 1), fmode, frow + k, fast_ok);
     }
 
+    // Outcomes of all pairs of positions; group g of row k ends up in bit k * GPR + g.
+    PairWords<M> pw;
+    float pmax = 0.0f;
+#pragma unroll
+    for (int k = RB - 1; k >= 0; --k) {
+        const float fr = NORM_COLS ? 0.0f : frow[k];
+#pragma unroll
+        for (int g = GPR - 1; g >= 0; --g) {
+            float p[M], q[M];
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const int e = g * M + a;
+                const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr;
+                p[a] = w * f;
+                q[a] = fmaf(w, f, -p[a]);
+                pmax = fmaxf(pmax, p[a]);
+            }
+            push_group<M>(pw, p, q);
+            __builtin_amdgcn_sched_barrier(0);   // one group at a time keeps the register count down
+        }
+    }
+    uint32_t keep[M];
+    keep_words<M>(pw, keep);
+
+    // as in nm_half_rows_kernel
+    const bool exact_path = __builtin_amdgcn_ballot_w64(!fast_ok || !(pmax < INFINITY)) != 0;
 #pragma unroll
     for (int k = 0; k < RB; ++k) {
         const int64_t r = by * RB + k;
         if (r >= rows)
             break;
-        float pmin = kHugeScore, pmax = 0.0f;
-        uint32_t kept = 0;
-#pragma unroll
-        for (int g = 0; g < UW / M; ++g) {
-            float p[M], q[M];
-#pragma unroll
-            for (int a = 0; a < M; ++a) {
-                const int e = g * M + a;
-                const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr[k];
-                p[a] = w * f;
-                q[a] = fmaf(w, f, -p[a]);
-                pmin = fminf(pmin, p[a]);
-                pmax = fmaxf(pmax, p[a]);
-            }
-            keep_top_half<M>(p, q, [&](int a, lanemask_t keep) {
-                const int e = g * M + a;
-                clear_unless<DT>(v[k][e / EPV], e % EPV, keep);
-                if constexpr (WITH_MASK)
-                    kept |= __builtin_amdgcn_inverse_ballot_w64(keep) ? (1u << e) : 0u;
-            });
-        }
-        // as in nm_half_rows_kernel: leave the fast path when a score is out of its exact range
-        bool exact_path = false;
-        if (__builtin_amdgcn_fcmpf(pmin, kTinyScore, kCmpLt) | ~__builtin_amdgcn_fcmpf(pmax, kHugeScore, kCmpLt)) {
-            bool risky = false;
-#pragma unroll 1
-            for (int e = 0; e < UW; ++e)
-                risky |= score_needs_f64(abs_at<DT>(W, r, c0 + e, ld),
-                                         NORM_COLS ? factor_of(norms[c0 + e], fmode) : fr[k]);
-            exact_path = __builtin_amdgcn_ballot_w64(risky) != 0;
-        }
+        uint32_t kept = 0;   // keep flags of the row's UW columns
         if (exact_path) {
-            kept = 0;
 #pragma unroll 1
-            for (int g = 0; g < UW / M; ++g) {
+            for (int g = 0; g < GPR; ++g) {
                 double sc[M];
 #pragma unroll
                 for (int a = 0; a < M; ++a)
                     sc[a] = (double)abs_at<DT>(W, r, c0 + g * M + a, ld) *
-                            (double)(NORM_COLS ? factor_of(norms[c0 + g * M + a], fmode) : fr[k]);
+                            (double)factor_of(norms[NORM_COLS ? c0 + g * M + a : r], fmode);
                 const uint32_t bits = nm_keep_bits<M>(sc, M / 2);
 #pragma unroll
                 for (int a = 0; a < M; ++a)
@@ -311,11 +321,31 @@ __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
                         zero_at<DT>(W, r, c0 + g * M + a, ld);
                 kept |= bits << (g * M);
             }
-        }
+        } else {
+            uint32_t m[UW];   // all-ones where column e of the row is kept
 #pragma unroll
-        for (int j = 0; j < NV; ++j)
-            if (active && !exact_path)
-                __builtin_nontemporal_store(v[k][j], reinterpret_cast<u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
+            for (int e = 0; e < UW; ++e)
+                m[e] = spread_bit(keep[e % M], k * GPR + e / M);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                if constexpr (DT == DASS_BF16) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[k][j][i] &= (m[j * 8 + 2 * i] & 0x0000ffffu) | (m[j * 8 + 2 * i + 1] & 0xffff0000u);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[k][j][i] &= m[j * 4 + i];
+                }
+                if (active)
+                    __builtin_nontemporal_store(v[k][j], reinterpret_cast<u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
+            }
+            if constexpr (WITH_MASK) {
+#pragma unroll
+                for (int e = 0; e < UW; ++e)
+                    kept |= m[e] & (1u << e);
+            }
+        }
         if constexpr (WITH_MASK) {
             if constexpr (UW >= 8) {
                 if (active) {
@@ -574,7 +604,7 @@ static nm_kernel_t pick_kernel_m(int m, int group_axis, int norm_axis)
 }
 
 using nm_half_kernel_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint8_t *,
-                                  int64_t);
+                                  uint32_t);
 
 template <int DT, int M, bool WITH_MASK>
 static nm_half_kernel_t pick_half_kernel(int group_axis, int norm_axis)
@@ -645,19 +675,25 @@ extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, i
                             : pick_half_kernel_mask<DASS_F32>(mask_out != nullptr, m, group_axis, norm_axis);
         int64_t slots, batches;   // one thread per (column slot, row batch), no loop
         if (group_axis == DASS_AXIS_COLS) {
-            const int uw = m > epv ? m : epv;
+            const int uw = m > epv ? m : epv, rb = kHalfColsRows / (uw / epv);
             slots = cols / uw;
-            batches = (rows + (uw == epv ? 4 : 2) - 1) / (uw == epv ? 4 : 2);
+            batches = (rows + rb - 1) / rb;
         } else {
             slots = cols / epv;
             const int gb = m >= 4 ? 1 : 2;
             batches = (rows / m + gb - 1) / gb;
         }
-        const int64_t nbx = (slots + kBlock - 1) / kBlock;
+        // Workgroup width: the widest of 256, 128, 64 that leaves the fewest idle lanes in the
+        // last workgroup of a row (e.g. 1376 slots: 6 x 256 idles 10 %, 11 x 128 only 2 %).
+        int block = kBlock;
+        for (int cand = kBlock / 2; cand >= 64; cand /= 2)
+            if ((slots + cand - 1) / cand * cand < (slots + block - 1) / block * block)
+                block = cand;
+        const int64_t nbx = (slots + block - 1) / block;
         if (nbx * batches > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: matrix too large for one launch", fn);
-        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbx * batches)), dim3(kBlock), 0, stream, W, rows, cols, ld,
-                           norms, fmode, mask_out, nbx);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nbx * batches)), dim3(block), 0, stream, W, rows, cols, ld,
+                           norms, fmode, mask_out, (uint32_t)nbx);
         return check_launch("N:M kernel");
     }
 

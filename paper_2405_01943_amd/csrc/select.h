@@ -4,6 +4,10 @@
 
 #include "dass_internal.h"
 
+// Stage 2 compares exact scores built from individually rounded products and differences: the
+// compiler must not fuse a multiply into a neighbouring add or subtract anywhere in this code.
+#pragma clang fp contract(off)
+
 namespace dass {
 
 // 32-bit words that hold `n` consecutive elements of dtype DT.
@@ -67,72 +71,94 @@ __device__ __forceinline__ uint32_t nm_keep_bits(const double *s, int min_wins)
 // ---------------------------------------------------------------------------
 // Fast exact selection for the n_keep = m / 2 patterns (1:2, 2:4, 4:8).
 //
-// The exact score |w| * f of an f32 (or bf16) weight and an f32 factor is kept
-// as the unevaluated sum p + q of two f32: p = fl(|w| f) and q = fma(|w|, f, -p),
-// the rounding error of p, which is itself an f32 whenever no underflow gets in
-// the way (callers check that).  Rounding is monotonic, so scores order like
-// the pairs (p, q) taken lexicographically.
+// The exact score |w| * f of an f32 (or bf16) weight and an f32 factor is kept as the
+// unevaluated sum p + q of two f32: p = fl(|w| f') and q = fma(|w|, f', -p), the rounding
+// error of p, with f' = 2^64 f.  The error term is a multiple of ulp(w) ulp(f'); with
+// f' >= 2^23 (f >= 2^-41) that is at least 2^-149 even for a subnormal weight, so q is always
+// an f32 and p + q is the exact product.  Factors outside [2^-41, 2^64) other than 0, and
+// products that overflow, send a wavefront to the f64 path instead (callers check).
 //
-// A comparison of two scores is made for all 64 lanes at once and lands in a
-// scalar register as a lane mask; everything after it (who beats whom, who has
-// enough wins) is bitwise logic on such masks, done by the scalar unit.
+// Rounding is monotonic, so scores order like the pairs (p, q) taken lexicographically:
+// with d = pa - pb and dq = qa - qb, both correctly signed, t = 4 d + dq has the sign of the
+// difference of the exact scores (|dq| < 2 |d| whenever d != 0, and t = dq when d == 0).
+//
+// One thread holds G groups of M positions.  For every pair of positions the outcome in
+// group g is bit g of one 32-bit word, so the logic that turns outcomes into keep flags runs
+// on all of the thread's groups at once.
 // ---------------------------------------------------------------------------
-typedef uint64_t lanemask_t;
+constexpr float kFactorScale = 0x1p+64f;
+constexpr float kFactorMin = 0x1p-41f, kFactorMax = 0x1p+64f;   // nonzero factors the fast path takes: [min, max)
 
-enum { kCmpEq = 1, kCmpGt = 2, kCmpGe = 3, kCmpLt = 4 };   // ordered f32 predicates of the compare builtin
-
-// Lanes where score a >= score b (a sits before b in its group, so a also wins ties).
-__device__ __forceinline__ lanemask_t score_ge(float pa, float qa, float pb, float qb)
+__device__ __forceinline__ bool factor_in_fast_range(float f)
 {
-    const lanemask_t gt = __builtin_amdgcn_fcmpf(pa, pb, kCmpGt);
-    const lanemask_t eq = __builtin_amdgcn_fcmpf(pa, pb, kCmpEq);
-    const lanemask_t ge = __builtin_amdgcn_fcmpf(qa, qb, kCmpGe);
-    return gt | (eq & ge);
+    return f == 0.0f || (f >= kFactorMin && f < kFactorMax);
 }
 
-__device__ __forceinline__ lanemask_t majority3(lanemask_t x, lanemask_t y, lanemask_t z)
+template <int M>
+struct PairWords {
+    uint32_t w[M * (M - 1) / 2];   // pair (a, b), a < b, in the order (0,1) (0,2) .. (M-2,M-1)
+};
+
+// Shift the outcomes of one more group into the pair words: the new bit 0 of pair (a, b) is
+// set iff b's score is strictly greater than a's (on a tie the earlier position, a, ranks higher).
+template <int M>
+__device__ __forceinline__ void push_group(PairWords<M> &pw, const float *p, const float *q)
+{
+    int n = 0;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = a + 1; b < M; ++b) {
+            const float t = fmaf(p[a] - p[b], 4.0f, q[a] - q[b]);
+            pw.w[n] = __builtin_amdgcn_alignbit(pw.w[n], __float_as_uint(t), 31);   // (w << 1) | sign(t)
+            // Pin the word here: otherwise the compiler sinks every push below the caller's
+            // range check and keeps all scores of the thread live until then.
+            asm volatile("" : "+v"(pw.w[n]));
+            ++n;
+        }
+}
+
+__device__ __forceinline__ uint32_t majority3(uint32_t x, uint32_t y, uint32_t z)
 {
     return (x & y) | (z & (x | y));
 }
 
-// Calls apply(a, keep) for every position a of a group, where keep = lanes in which position
-// a is among the M / 2 best, i.e. beats at least M / 2 of the other M - 1 positions.  p, q: the
-// M scores of the group.  Positions are finished one after the other (for M = 8 with a
-// scheduling fence in between) so that only the comparisons with later positions stay live:
-// all 28 masks of an 8-group and their complements would not fit the scalar registers.
-template <int M, typename Apply>
-__device__ __forceinline__ void keep_top_half(const float *p, const float *q, Apply apply)
+// keep[a]: bit g set iff position a of group g is among the M / 2 best of its group, i.e.
+// ranks above at least M / 2 of the other M - 1 positions.  Bits above the thread's group
+// count are garbage.
+template <int M>
+__device__ __forceinline__ void keep_words(const PairWords<M> &pw, uint32_t *keep)
 {
     static_assert(M == 2 || M == 4 || M == 8, "patterns 1:2, 2:4 and 4:8");
-    lanemask_t beats[M][M];   // beats[a][b] for a < b: a ranks above b
+    auto pair_index = [](int a, int b) { return a * (2 * M - a - 1) / 2 + (b - a - 1); };   // a < b
 #pragma unroll
     for (int a = 0; a < M; ++a) {
-        lanemask_t x[M - 1];
+        uint32_t x[M - 1];   // x[.]: a ranks above the other position
         int n = 0;
 #pragma unroll
         for (int b = 0; b < a; ++b)
-            x[n++] = ~beats[b][a];
+            x[n++] = pw.w[pair_index(b, a)];
 #pragma unroll
-        for (int b = a + 1; b < M; ++b) {
-            beats[a][b] = score_ge(p[a], q[a], p[b], q[b]);
-            x[n++] = beats[a][b];
-        }
-        lanemask_t keep;
+        for (int b = a + 1; b < M; ++b)
+            x[n++] = ~pw.w[pair_index(a, b)];
         if constexpr (M == 2) {
-            keep = x[0];
+            keep[a] = x[0];
         } else if constexpr (M == 4) {
-            keep = majority3(x[0], x[1], x[2]);
+            keep[a] = majority3(x[0], x[1], x[2]);
         } else {
             // at least 4 of 7: carry-save adders; the weight-4 bit of the count is the answer
-            const lanemask_t s1 = x[0] ^ x[1] ^ x[2], c1 = majority3(x[0], x[1], x[2]);
-            const lanemask_t s2 = x[3] ^ x[4] ^ x[5], c2 = majority3(x[3], x[4], x[5]);
-            const lanemask_t c3 = majority3(s1, s2, x[6]);
-            keep = majority3(c1, c2, c3);
+            const uint32_t s1 = x[0] ^ x[1] ^ x[2], c1 = majority3(x[0], x[1], x[2]);
+            const uint32_t s2 = x[3] ^ x[4] ^ x[5], c2 = majority3(x[3], x[4], x[5]);
+            const uint32_t c3 = majority3(s1, s2, x[6]);
+            keep[a] = majority3(c1, c2, c3);
         }
-        apply(a, keep);
-        if constexpr (M == 8)
-            __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+// All-ones if bit `bit` of `word` is set, else 0.
+__device__ __forceinline__ uint32_t spread_bit(uint32_t word, int bit)
+{
+    return (uint32_t)__builtin_amdgcn_sbfe((int)word, bit, 1);
 }
 
 // 16-byte vector of raw words, the unit of every global access of stage 2.
