@@ -329,25 +329,19 @@ __global__ __launch_bounds__(256) void calib_pipe_kernel(
 
     __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
 
-    // ---- tile assignment: as in calib_mfma_kernel above
-    const int64_t n_tiles = tiles_t * tiles_n;
-    const int64_t per_xcd = (n_tiles + 7) / 8;
-    const int64_t lin = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (lin >= n_tiles)
+    // ---- tile assignment.  Consecutive workgroup ids go to different XCDs (8 of them, each
+    // with its own L2).  The tile grid is cut into patches of 4 token tiles x 8 neuron tiles; an
+    // XCD's 32 concurrent workgroups take one patch, so its L2 serves all but 3/16 of their reads.
+    // Patches are listed token-major and dealt round-robin to the XCDs: at any time all XCDs
+    // work on the same few token tiles, so X is fetched from HBM by one of them and found in
+    // the memory-side cache by the others (measured: +5 % over giving each XCD its own band).
+    constexpr int PT = 4, PN = 8;
+    const int64_t np_n = (tiles_n + PN - 1) / PN;
+    const int64_t idx = blockIdx.x / 8, within = idx % (PT * PN);
+    const int64_t patch = (idx / (PT * PN)) * 8 + blockIdx.x % 8;
+    const int64_t tile_t = (patch / np_n) * PT + within / PN, tile_n = (patch % np_n) * PN + within % PN;
+    if (tile_t >= tiles_t || tile_n >= tiles_n)
         return;
-    constexpr int BAND = 8;
-    const int64_t full_bands = tiles_n / BAND;
-    int64_t tile_t, tile_n;
-    if (lin < full_bands * BAND * tiles_t) {
-        const int64_t band = lin / (BAND * tiles_t), rem = lin % (BAND * tiles_t);
-        tile_t = rem / BAND;
-        tile_n = band * BAND + rem % BAND;
-    } else {
-        const int64_t rem = lin - full_bands * BAND * tiles_t;
-        const int64_t bw = tiles_n - full_bands * BAND;
-        tile_t = rem / bw;
-        tile_n = full_bands * BAND + rem % bw;
-    }
     const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -733,8 +727,13 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         const bool pipe_ok = d % P_BK == 0 && (int64_t)P_BM * ldx * 2 < 0x7fffffffLL &&
                              (int64_t)P_BN * ldw * 2 < 0x7fffffffLL;
         static_assert(BM == P_BM && BN == P_BN, "both bf16 kernels use the same tile grid");
+        // calib_pipe_kernel: whole 4 x 8 patches of tiles, dealt to the 8 XCDs
+        const int64_t patches = ((tiles_t + 3) / 4) * ((tiles_n + 7) / 8);
+        const int64_t pipe_blocks = (patches + 7) / 8 * 8 * 32;
+        if (pipe_ok && pipe_blocks > 0x7fffffffLL)
+            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
         if (pipe_ok)
-            launch_pipe((int)act, dim3((unsigned)blocks), stream, static_cast<const uint16_t *>(X), T, ldx,
+            launch_pipe((int)act, dim3((unsigned)pipe_blocks), stream, static_cast<const uint16_t *>(X), T, ldx,
                         static_cast<const uint16_t *>(Wgate), static_cast<const uint16_t *>(Wup), ldw, d,
                         d_int, sumsq, tiles_t, tiles_n);
         else
