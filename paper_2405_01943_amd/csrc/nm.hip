@@ -16,6 +16,8 @@
 //               scores as f64 products, selection by counting wins per lane.
 #include "select.h"
 
+#include <type_traits>
+
 #include <mutex>
 
 namespace dass {
@@ -109,7 +111,7 @@ __device__ __forceinline__ void zero_at(char *W, int64_t r, int64_t c, int64_t l
 // workgroup covers up to 256 such column slots, so rows are read and written in contiguous
 // pieces of up to 4 KB; every thread makes one pass and the grid covers the matrix (many small workgroups
 // keep HBM busier than a resident grid that loops).
-template <int DT, int M, bool NORM_ROWS, bool WITH_MASK>
+template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool OPTIMISTIC>
 __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
@@ -155,19 +157,37 @@ __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
 
         // Outcomes of all pairs of rows, one bit per column (column e ends up in bit e).
         PairWords<M> pw;
-        float pmax = 0.0f;
+        float pmax = 0.0f, dmin = 1.0f;
+        auto fill = [&](auto leading_only) {
+            constexpr bool LEADING_ONLY = decltype(leading_only)::value;
 #pragma unroll
-        for (int e = EPV - 1; e >= 0; --e) {
-            float p[M], q[M];
+            for (int e = EPV - 1; e >= 0; --e) {
+                float p[M], q[M];
 #pragma unroll
-            for (int a = 0; a < M; ++a) {
-                const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[a] : fc[e];
-                p[a] = w * f;
-                q[a] = fmaf(w, f, -p[a]);
-                pmax = fmaxf(pmax, p[a]);
+                for (int a = 0; a < M; ++a) {
+                    const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[a] : fc[e];
+                    p[a] = w * f;
+                    q[a] = LEADING_ONLY ? 0.0f : fmaf(w, f, -p[a]);
+                    pmax = fmaxf(pmax, p[a]);
+                }
+                push_group<M, LEADING_ONLY>(pw, p, q, dmin);
+                __builtin_amdgcn_sched_barrier(0);   // one column at a time keeps the register count down
             }
-            push_group<M>(pw, p, q);
-            __builtin_amdgcn_sched_barrier(0);   // one column at a time keeps the register count down
+        };
+        if constexpr (OPTIMISTIC) {
+            fill(std::true_type{});
+            if (__builtin_amdgcn_ballot_w64(dmin == 0.0f) != 0) {   // two equal leading terms somewhere
+                // (the weights pass through an empty asm so that the second pass recomputes its
+                // products instead of keeping all of the first pass's alive)
+#pragma unroll
+                for (int a = 0; a < M; ++a)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        asm volatile("" : "+v"(v[g][a][j]));
+                fill(std::false_type{});
+            }
+        } else {
+            fill(std::false_type{});
         }
         uint32_t keep[M];
         keep_words<M>(pw, keep);
@@ -233,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
 // Groups run along a row (contiguous): Down-Proj.  A thread owns the UW = max(EPV, M)
 // consecutive columns of NV 16-byte vectors and RB rows, RB * UW / M groups; the factors of
 // its columns are computed once.
-template <int DT, int M, bool NORM_COLS, bool WITH_MASK>
+template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool OPTIMISTIC>
 __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
@@ -276,24 +296,42 @@ __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
 
     // Outcomes of all pairs of positions; group g of row k ends up in bit k * GPR + g.
     PairWords<M> pw;
-    float pmax = 0.0f;
+    float pmax = 0.0f, dmin = 1.0f;
+    auto fill = [&](auto leading_only) {
+        constexpr bool LEADING_ONLY = decltype(leading_only)::value;
 #pragma unroll
-    for (int k = RB - 1; k >= 0; --k) {
-        const float fr = NORM_COLS ? 0.0f : frow[k];
+        for (int k = RB - 1; k >= 0; --k) {
+            const float fr = NORM_COLS ? 0.0f : frow[k];
 #pragma unroll
-        for (int g = GPR - 1; g >= 0; --g) {
-            float p[M], q[M];
+            for (int g = GPR - 1; g >= 0; --g) {
+                float p[M], q[M];
 #pragma unroll
-            for (int a = 0; a < M; ++a) {
-                const int e = g * M + a;
-                const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr;
-                p[a] = w * f;
-                q[a] = fmaf(w, f, -p[a]);
-                pmax = fmaxf(pmax, p[a]);
+                for (int a = 0; a < M; ++a) {
+                    const int e = g * M + a;
+                    const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr;
+                    p[a] = w * f;
+                    q[a] = LEADING_ONLY ? 0.0f : fmaf(w, f, -p[a]);
+                    pmax = fmaxf(pmax, p[a]);
+                }
+                push_group<M, LEADING_ONLY>(pw, p, q, dmin);
+                __builtin_amdgcn_sched_barrier(0);   // one group at a time keeps the register count down
             }
-            push_group<M>(pw, p, q);
-            __builtin_amdgcn_sched_barrier(0);   // one group at a time keeps the register count down
         }
+    };
+    if constexpr (OPTIMISTIC) {
+        fill(std::true_type{});
+        if (__builtin_amdgcn_ballot_w64(dmin == 0.0f) != 0) {   // two equal leading terms somewhere
+#pragma unroll
+            for (int k = 0; k < RB; ++k)   // see nm_half_rows_kernel
+#pragma unroll
+                for (int j = 0; j < NV; ++j)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        asm volatile("" : "+v"(v[k][j][i]));
+            fill(std::false_type{});
+        }
+    } else {
+        fill(std::false_type{});
     }
     uint32_t keep[M];
     keep_words<M>(pw, keep);
@@ -606,32 +644,41 @@ static nm_kernel_t pick_kernel_m(int m, int group_axis, int norm_axis)
 using nm_half_kernel_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint8_t *,
                                   uint32_t);
 
+// With 8 positions per group the 28 comparisons dominate the kernel, so it first compares the
+// leading terms only (OPTIMISTIC) when ties between them are unlikely: the factor varies
+// inside a group, i.e. it runs along the group axis and alpha is not 0.  A factor that is
+// constant inside the groups leaves bf16 magnitudes to tie all the time; then, and for
+// m < 8 where the kernel is bound by memory anyway, both terms are compared straight away.
 template <int DT, int M, bool WITH_MASK>
-static nm_half_kernel_t pick_half_kernel(int group_axis, int norm_axis)
+static nm_half_kernel_t pick_half_kernel(int group_axis, int norm_axis, bool varying_factor)
 {
+    if (M == 8 && varying_factor)
+        return group_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK, M == 8>
+                                            : nm_half_rows_kernel<DT, M, true, WITH_MASK, M == 8>;
     if (group_axis == DASS_AXIS_COLS)
-        return norm_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK>
-                                           : nm_half_cols_kernel<DT, M, false, WITH_MASK>;
-    return norm_axis == DASS_AXIS_ROWS ? nm_half_rows_kernel<DT, M, true, WITH_MASK>
-                                       : nm_half_rows_kernel<DT, M, false, WITH_MASK>;
+        return norm_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK, false>
+                                           : nm_half_cols_kernel<DT, M, false, WITH_MASK, false>;
+    return norm_axis == DASS_AXIS_ROWS ? nm_half_rows_kernel<DT, M, true, WITH_MASK, false>
+                                       : nm_half_rows_kernel<DT, M, false, WITH_MASK, false>;
 }
 
 template <int DT, bool WITH_MASK>
-static nm_half_kernel_t pick_half_kernel_m(int m, int group_axis, int norm_axis)
+static nm_half_kernel_t pick_half_kernel_m(int m, int group_axis, int norm_axis, bool varying_factor)
 {
     switch (m) {
-    case 2: return pick_half_kernel<DT, 2, WITH_MASK>(group_axis, norm_axis);
-    case 4: return pick_half_kernel<DT, 4, WITH_MASK>(group_axis, norm_axis);
-    case 8: return pick_half_kernel<DT, 8, WITH_MASK>(group_axis, norm_axis);
+    case 2: return pick_half_kernel<DT, 2, WITH_MASK>(group_axis, norm_axis, varying_factor);
+    case 4: return pick_half_kernel<DT, 4, WITH_MASK>(group_axis, norm_axis, varying_factor);
+    case 8: return pick_half_kernel<DT, 8, WITH_MASK>(group_axis, norm_axis, varying_factor);
     }
     return nullptr;
 }
 
 template <int DT>
-static nm_half_kernel_t pick_half_kernel_mask(bool with_mask, int m, int group_axis, int norm_axis)
+static nm_half_kernel_t pick_half_kernel_mask(bool with_mask, int m, int group_axis, int norm_axis,
+                                              bool varying_factor)
 {
-    return with_mask ? pick_half_kernel_m<DT, true>(m, group_axis, norm_axis)
-                     : pick_half_kernel_m<DT, false>(m, group_axis, norm_axis);
+    return with_mask ? pick_half_kernel_m<DT, true>(m, group_axis, norm_axis, varying_factor)
+                     : pick_half_kernel_m<DT, false>(m, group_axis, norm_axis, varying_factor);
 }
 
 }  // namespace dass
@@ -670,9 +717,10 @@ extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, i
     if (2 * n_keep == m && m <= 8 && (alpha == 0.0 || alpha == 0.5 || alpha == 1.0)) {
         const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
         const int epv = vec_elems(dt);
+        const bool varying = norm_axis == group_axis && alpha != 0.0;
         nm_half_kernel_t kernel =
-            dt == DASS_BF16 ? pick_half_kernel_mask<DASS_BF16>(mask_out != nullptr, m, group_axis, norm_axis)
-                            : pick_half_kernel_mask<DASS_F32>(mask_out != nullptr, m, group_axis, norm_axis);
+            dt == DASS_BF16 ? pick_half_kernel_mask<DASS_BF16>(mask_out != nullptr, m, group_axis, norm_axis, varying)
+                            : pick_half_kernel_mask<DASS_F32>(mask_out != nullptr, m, group_axis, norm_axis, varying);
         int64_t slots, batches;   // one thread per (column slot, row batch), no loop
         if (group_axis == DASS_AXIS_COLS) {
             const int uw = m > epv ? m : epv, rb = kHalfColsRows / (uw / epv);

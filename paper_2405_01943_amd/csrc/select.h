@@ -101,15 +101,24 @@ struct PairWords {
 
 // Shift the outcomes of one more group into the pair words: the new bit 0 of pair (a, b) is
 // set iff b's score is strictly greater than a's (on a tie the earlier position, a, ranks higher).
-template <int M>
-__device__ __forceinline__ void push_group(PairWords<M> &pw, const float *p, const float *q)
+// LEADING_ONLY compares the leading terms p alone, which decides every pair whose leading
+// terms differ, and lowers dmin to 0 when two are equal: the caller must then push all of
+// the thread's groups again with both terms.
+template <int M, bool LEADING_ONLY>
+__device__ __forceinline__ void push_group(PairWords<M> &pw, const float *p, const float *q, float &dmin)
 {
     int n = 0;
 #pragma unroll
     for (int a = 0; a < M; ++a)
 #pragma unroll
         for (int b = a + 1; b < M; ++b) {
-            const float t = fmaf(p[a] - p[b], 4.0f, q[a] - q[b]);
+            float t;
+            if constexpr (LEADING_ONLY) {
+                t = p[a] - p[b];
+                dmin = fminf(dmin, fabsf(t));
+            } else {
+                t = fmaf(p[a] - p[b], 4.0f, q[a] - q[b]);
+            }
             pw.w[n] = __builtin_amdgcn_alignbit(pw.w[n], __float_as_uint(t), 31);   // (w << 1) | sign(t)
             // Pin the word here: otherwise the compiler sinks every push below the caller's
             // range check and keeps all scores of the thread live until then.

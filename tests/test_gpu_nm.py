@@ -119,6 +119,38 @@ def test_nm_extreme_magnitudes(gpu_device, dtype, axes, n_keep, m):
         assert np.array_equal(mask.cpu().numpy(), want_mask)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+@pytest.mark.parametrize("n_keep,m", [(2, 4), (4, 8)])
+def test_nm_near_ties_decided_below_f32_precision(gpu_device, dtype, axes, n_keep, m):
+    """Groups whose scores agree to f32 precision and differ only below it: weight k of a group
+    is 1 + k/128 and its norm is fl32(P / weight), so all m products are P up to an f32 rounding
+    error.  Only a comparison of the exact products ranks them like the oracle."""
+    n_groups, lines = 96, 64
+    g = torch.Generator(device="cpu").manual_seed(5 * m + (axes[0] == "rows"))
+    k = torch.stack([torch.randperm(m, generator=g) for _ in range(n_groups)]).reshape(-1)   # weight index along d_int
+    w_line = (1.0 + k.to(torch.float64) / 128.0)                                             # exact in bf16
+    P = torch.exp(torch.rand(n_groups, generator=g, dtype=torch.float64) * 8 - 4).repeat_interleave(m)
+    nrm = (P / w_line).to(torch.float32)
+    sign = torch.where(torch.rand((lines, n_groups * m), generator=g) < 0.5, -1.0, 1.0).to(torch.float64)
+    W = (w_line[None, :] * sign)                                                             # [lines, d_int]
+    if axes[0] == "rows":
+        W = W.t().contiguous()                                                               # groups down the rows
+    W = W.to(dtype)
+    # the construction does what it says: many pairs inside a group share the f32 product
+    p32 = (w_line.to(torch.float32) * nrm).reshape(n_groups, m)
+    exact = (w_line * nrm.to(torch.float64)).reshape(n_groups, m)
+    same_p = (p32[:, :, None] == p32[:, None, :]) & (exact[:, :, None] != exact[:, None, :])
+    assert same_p.any(dim=(1, 2)).float().mean() > 0.5
+    want, want_mask = oracle.mask_nm(to_np32(W), nrm.numpy(), axes[0], axes[1], 1.0, n_keep, m, want_mask=True)
+    Wg = W.to(gpu_device)
+    mask = torch.zeros((Wg.shape[0], Wg.shape[1] // 8), dtype=torch.uint8, device=gpu_device)
+    dass.score_mask_nm(Wg, nrm.to(gpu_device), axes[0], axes[1], 1.0, n_keep, m, mask_out=mask)
+    torch.cuda.synchronize()
+    assert bits_equal(Wg, want), first_mismatch(Wg, want)
+    assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
 def test_nm_tiny_config_all_three_matrices(gpu_device):
     """Config 'tiny' (f32, d=256, d_int=688): Gate, Up with alpha 0.5 down rows; Down with alpha 1."""
     cfg = synth.CONFIGS["tiny"]
