@@ -316,7 +316,7 @@ template <int ACT>
 __global__ __launch_bounds__(256) void calib_pipe_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
     const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
-    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n)
+    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
 {
     constexpr int BM = P_BM, BN = P_BN, BK = P_BK, NS = P_NS, WN = 2;
     constexpr int TM = 128, TN = 64, MI = 4, NI = 2;   // wavefront tile: 128 tokens x 64 neurons
@@ -332,14 +332,23 @@ __global__ __launch_bounds__(256) void calib_pipe_kernel(
     // ---- tile assignment.  Consecutive workgroup ids go to different XCDs (8 of them, each
     // with its own L2).  The tile grid is cut into patches of 4 token tiles x 8 neuron tiles; an
     // XCD's 32 concurrent workgroups take one patch, so its L2 serves all but 3/16 of their reads.
-    // Patches are listed token-major and dealt round-robin to the XCDs: at any time all XCDs
-    // work on the same few token tiles, so X is fetched from HBM by one of them and found in
-    // the memory-side cache by the others (measured: +5 % over giving each XCD its own band).
+    // Patches are dealt round-robin to the XCDs from a list ordered so that the 8 patches in
+    // flight share data through the memory-side cache:
+    //   super_rows = 1: token-major.  The 8 patches lie in one row of patches: X is fetched
+    //     from HBM by one XCD and found in the cache by the others, and the weights stay
+    //     cached from one row to the next as long as both matrices fit (measured: +5 % over
+    //     giving each XCD its own band of neurons).
+    //   super_rows = R > 1, for weights too large to stay cached: rows of patches are taken R
+    //     at a time, and inside such a super-row the patch columns are outermost.  The 8 patches
+    //     share one patch column of the weights, fetched once per super-row, and the super-row's
+    //     X (R x 8 MB at d = 4096) stays cached while the columns sweep past.
     constexpr int PT = 4, PN = 8;
-    const int64_t np_n = (tiles_n + PN - 1) / PN;
+    const int64_t np_n = (tiles_n + PN - 1) / PN, np_t = (tiles_t + PT - 1) / PT;
     const int64_t idx = blockIdx.x / 8, within = idx % (PT * PN);
     const int64_t patch = (idx / (PT * PN)) * 8 + blockIdx.x % 8;
-    const int64_t tile_t = (patch / np_n) * PT + within / PN, tile_n = (patch % np_n) * PN + within % PN;
+    const int64_t sr = patch / (np_n * super_rows), rem = patch % (np_n * super_rows);
+    const int64_t prow = sr * super_rows + rem % super_rows, pcol = rem / super_rows;
+    const int64_t tile_t = prow * PT + within / PN, tile_n = pcol * PN + within % PN;
     if (tile_t >= tiles_t || tile_n >= tiles_n)
         return;
     const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
@@ -645,25 +654,25 @@ static void launch_mfma(int act, dim3 grid, hipStream_t stream, const uint16_t *
 
 static void launch_pipe(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
                         const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
-                        float *sumsq, int64_t tiles_t, int64_t tiles_n)
+                        float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
 {
     const dim3 block(256);
     switch (act) {
     case DASS_ACT_SILU:
         hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_SILU>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw, d,
-                           d_int, sumsq, tiles_t, tiles_n);
+                           d_int, sumsq, tiles_t, tiles_n, super_rows);
         break;
     case DASS_ACT_GELU_TANH:
         hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_GELU_TANH>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw,
-                           d, d_int, sumsq, tiles_t, tiles_n);
+                           d, d_int, sumsq, tiles_t, tiles_n, super_rows);
         break;
     case DASS_ACT_GELU_ERF:
         hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_GELU_ERF>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw,
-                           d, d_int, sumsq, tiles_t, tiles_n);
+                           d, d_int, sumsq, tiles_t, tiles_n, super_rows);
         break;
     default:
         hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_RELU>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw, d,
-                           d_int, sumsq, tiles_t, tiles_n);
+                           d_int, sumsq, tiles_t, tiles_n, super_rows);
         break;
     }
 }
@@ -727,15 +736,17 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         const bool pipe_ok = d % P_BK == 0 && (int64_t)P_BM * ldx * 2 < 0x7fffffffLL &&
                              (int64_t)P_BN * ldw * 2 < 0x7fffffffLL;
         static_assert(BM == P_BM && BN == P_BN, "both bf16 kernels use the same tile grid");
-        // calib_pipe_kernel: whole 4 x 8 patches of tiles, dealt to the 8 XCDs
-        const int64_t patches = ((tiles_t + 3) / 4) * ((tiles_n + 7) / 8);
+        // calib_pipe_kernel: whole 4 x 8 patches of tiles, dealt to the 8 XCDs; rows of patches
+        // in groups of 8 when Wgate + Wup exceed the 256 MB memory-side cache (see the kernel)
+        const int super_rows = 2 * d_int * d * 2 > (256LL << 20) ? 8 : 1;
+        const int64_t patches = ((tiles_t + 3) / 4 + super_rows - 1) / super_rows * super_rows * ((tiles_n + 7) / 8);
         const int64_t pipe_blocks = (patches + 7) / 8 * 8 * 32;
         if (pipe_ok && pipe_blocks > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
         if (pipe_ok)
             launch_pipe((int)act, dim3((unsigned)pipe_blocks), stream, static_cast<const uint16_t *>(X), T, ldx,
                         static_cast<const uint16_t *>(Wgate), static_cast<const uint16_t *>(Wup), ldw, d,
-                        d_int, sumsq, tiles_t, tiles_n);
+                        d_int, sumsq, tiles_t, tiles_n, super_rows);
         else
             launch_mfma<BM, BN, BK, 4, 2, 1>((int)act, dim3((unsigned)blocks), stream,
                                              static_cast<const uint16_t *>(X), T, ldx,
