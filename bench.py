@@ -38,10 +38,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; see profiles/).  A figure only stands while the source
 # of its kernel is the one the counters were taken on; otherwise `traffic` is null.
 MEASURED_TRAFFIC = {
-    "stage1": {"sources": ("calib.hip",), "sha256": "45c428a428301f72430fc4c3cea6d0fc1da602d8d59523a714ac73a461f2ab84",
-               "bytes": (34007400 * 2.0 + 88064) * 1024},
-    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "df09b54dce4d868486058c525de421ee0ca46c38a5ae515f5375809151066baf",
-               "bytes": (2 * (44423.5 * 2.0 + 88065) + (44529.0 * 2.0 + 88064)) * 1024},
+    "stage1": {"sources": ("calib.hip",), "sha256": "254476520601eedef04d1d91f87a1b75efeb38af6fb87f2f5503c5f1d42f65bf",
+               "bytes": (34629200 * 2.0 + 88064) * 1024},
+    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "5a9a45c21f96c8ad5177462443b6efebb1bc79ddfe794006a56ac60ccf051398",
+               "bytes": (2 * (44419.6 * 2.0 + 88064.6) + (44533.0 * 2.0 + 88064.6)) * 1024},
 }
 
 
