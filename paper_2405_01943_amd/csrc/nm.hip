@@ -28,17 +28,6 @@ constexpr int kHalfColsRows = 4;   // 16-byte vectors per thread of nm_half_cols
 // ---------------------------------------------------------------------------
 // n_keep = m / 2, factor computed in the kernel
 // ---------------------------------------------------------------------------
-enum { kFactorOne = 0, kFactorNorm = 1, kFactorSqrt = 2 };
-
-// f = norm^alpha for alpha = 0, 1, 0.5.  sqrtf is the correctly rounded f32 square root
-// (this file is built without fast-math), which equals the f64 square root rounded to f32.
-__device__ __forceinline__ float factor_of(float norm, int fmode)
-{
-    if (fmode == kFactorSqrt)
-        return sqrtf(norm);
-    return fmode == kFactorNorm ? norm : 1.0f;
-}
-
 // N factors at once from the norms at src[0..N): all loads are issued before the first use,
 // and the exponent is tested once.  ok is cleared when a factor is outside the fast range;
 // the factors come back scaled by kFactorScale.  VEC: src is 16-byte aligned and differs from
@@ -74,17 +63,6 @@ __device__ __forceinline__ void scaled_factors(const float *__restrict__ src, in
     for (int i = 0; i < N; ++i) {
         ok &= factor_in_fast_range(f[i]);
         f[i] *= kFactorScale;
-    }
-}
-
-template <int DT>
-__device__ __forceinline__ float elem_of(const u32x4 &v, int e)   // element e of a 16-byte vector, as f32
-{
-    if constexpr (DT == DASS_BF16) {
-        const uint32_t w = v[e >> 1];
-        return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
-    } else {
-        return __uint_as_float(v[e]);
     }
 }
 

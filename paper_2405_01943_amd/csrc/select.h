@@ -173,6 +173,38 @@ __device__ __forceinline__ uint32_t spread_bit(uint32_t word, int bit)
 // 16-byte vector of raw words, the unit of every global access of stage 2.
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
+enum { kFactorOne = 0, kFactorNorm = 1, kFactorSqrt = 2 };
+
+// f = norm^alpha for alpha = 0, 1, 0.5.  sqrtf is the correctly rounded f32 square root
+// (this file is built without fast-math), which equals the f64 square root rounded to f32.
+__device__ __forceinline__ float factor_of(float norm, int fmode)
+{
+    if (fmode == kFactorSqrt)
+        return sqrtf(norm);
+    return fmode == kFactorNorm ? norm : 1.0f;
+}
+
+template <int DT>
+__device__ __forceinline__ float elem_of(const u32x4 &v, int e)   // element e of a 16-byte vector, as f32
+{
+    if constexpr (DT == DASS_BF16) {
+        const uint32_t w = v[e >> 1];
+        return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+    } else {
+        return __uint_as_float(v[e]);
+    }
+}
+
+// Element e of a 16-byte vector becomes +0 when `drop` is set; plain mask arithmetic, no branch.
+template <int DT>
+__device__ __forceinline__ void zero_lane_if(u32x4 &v, int e, bool drop)
+{
+    if constexpr (DT == DASS_BF16)
+        v[e >> 1] &= drop ? ((e & 1) ? 0x0000ffffu : 0xffff0000u) : 0xffffffffu;
+    else
+        v[e] &= drop ? 0u : 0xffffffffu;
+}
+
 struct alignas(16) Vec16 {
     uint32_t w[4];
 };

@@ -15,6 +15,8 @@
 // wanted number of positions the index passes are skipped.
 #include "select.h"
 
+#include <type_traits>
+
 namespace dass {
 
 constexpr int kUBlock = 256;
@@ -412,6 +414,487 @@ __global__ __launch_bounds__(kUBlock) void unstructured_rows_kernel(
     }
 }
 
+
+// ===========================================================================
+// Line-resident kernels: lines of up to 16384 (bf16) / 8192 (f32) weights with alpha in
+// {0, 0.5, 1}.  A 1024-thread workgroup holds 8 lines in its registers, so the weights are read
+// once and written once; all selection passes run on the registers.
+//
+// Order of positions in a line: (score descending, index ascending), encoded as a composite
+// of three 32-bit fields (A, B, C) compared lexicographically, larger = kept first:
+//   A, B  the exact score: the two-term f32 form of select.h (A = bits of p, B = the error term
+//         q mapped to an unsigned integer that grows with q; rounding is monotonic, so p orders
+//         the scores and q orders those with equal p), or, when a factor or a product leaves
+//         the range in which that form is exact, the high and low words of the f64 product;
+//   C     0xFFFF - index (lines are shorter than 65536).
+// The threshold (the n_keep-th largest composite) is found digit by digit, most significant
+// first: 11 + 11 + 10 bits for A and for B, 11 + 5 for C, with one 2048-bin histogram per line
+// and pass.  Almost always the first three passes settle it: the search stops as soon as every
+// candidate left in the chosen bin is wanted.
+// ===========================================================================
+constexpr int kLrBins = 2048;
+constexpr int kLrLines = 8;
+constexpr int kLrPasses = 8;
+constexpr int kLrThreads = 1024;
+constexpr int kLrVecs = 16;   // 16-byte vectors held by a thread
+
+struct LrState {
+    uint32_t a, b, c;   // decided digits of the threshold, undecided bits 0
+    uint32_t need;      // rank still wanted among the candidates (>= 1)
+    uint32_t open;      // 1 until the threshold is known
+    uint32_t pad[3];
+};
+
+struct LrPass {
+    int field, shift, width;
+};
+__device__ __forceinline__ LrPass lr_pass(int pass)
+{
+    if (pass < 6) {
+        const int k = pass % 3;
+        return {pass / 3, k == 0 ? 21 : k == 1 ? 10 : 0, k == 2 ? 10 : 11};
+    }
+    return {2, pass == 6 ? 5 : 0, pass == 6 ? 11 : 5};
+}
+
+__device__ __forceinline__ uint32_t lr_mono(float q)   // unsigned integer that grows with q
+{
+    const uint32_t b = __float_as_uint(q);
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+
+__device__ __forceinline__ bool lr_keep(const LrState &st, uint32_t a, uint32_t b, uint32_t c)
+{
+    // all three fields are read and compared unconditionally: straight-line code
+    const uint32_t ta = st.a, tb = st.b, tc = st.c;
+    return (a > ta) | ((a == ta) & ((b > tb) | ((b == tb) & (c >= tc))));
+}
+
+__device__ __forceinline__ uint32_t lr_uniform(uint32_t x)   // a value every lane agrees on, in a scalar register
+{
+    return __builtin_amdgcn_readfirstlane(x);
+}
+
+// One wavefront finds, in the 2048-bin histogram of a line, the bin that holds the need-th
+// largest candidate and updates the line's state.  Lane l owns bins 2047 - 32 l .. 2016 - 32 l.
+// Returns (on every lane) whether a bin at or above `alarm_bin` is occupied.
+__device__ __forceinline__ bool lr_settle(const uint32_t *hist, LrState *state, const LrPass &ps, int pass,
+                                          uint32_t alarm_bin)
+{
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));   // keeps the per-lane bin numbers out of the caller's loop-invariant registers
+    const LrState st = *state;
+    uint32_t h[32], sum = 0;
+    bool alarm = false;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {   // ascending addresses: h[31 - 4q - 3 .. 31 - 4q]
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(hist + kLrBins - 32 * (lane + 1) + 4 * q);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            h[31 - 4 * q - i] = x[i];
+            sum += x[i];
+            alarm |= x[i] != 0 && (uint32_t)(kLrBins - 32 * (lane + 1)) + (uint32_t)(4 * q + i) >= alarm_bin;
+        }
+    }
+    const uint32_t incl = wave_inclusive_scan(sum);
+    uint32_t excl = incl - sum;
+    uint32_t my_digit = 0xFFFFFFFFu, my_above = 0, my_inside = 0;
+    if (excl < st.need && st.need <= incl) {
+        uint32_t my_j = 32;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {   // h[j] counts bin 2047 - 32 lane - j
+            if (my_j == 32 && st.need <= excl + h[j]) {
+                my_j = j;
+                my_above = excl;
+                my_inside = h[j];
+            }
+            excl += h[j];
+        }
+        my_digit = kLrBins - 1 - 32 * lane - my_j;
+    }
+    const uint64_t found = __ballot(my_digit != 0xFFFFFFFFu);   // exactly one lane: 1 <= need <= candidates
+    const int src = found ? __ffsll((long long)found) - 1 : 0;
+    const uint32_t digit = __shfl(my_digit, src, 64), above = __shfl(my_above, src, 64),
+                   inside = __shfl(my_inside, src, 64);
+    if (lane == 0) {
+        LrState n = st;
+        n.need = st.need - above;
+        const uint32_t d = digit << ps.shift;
+        if (ps.field == 0)
+            n.a |= d;
+        else if (ps.field == 1)
+            n.b |= d;
+        else
+            n.c |= d;
+        // every candidate left in the bin is wanted (always so after the last pass: composites are unique)
+        if (n.need == inside || pass == kLrPasses - 1)
+            n.open = 0;
+        *state = n;
+    }
+    return __ballot(alarm) != 0;
+}
+
+enum { kLrDown = 0, kLrGate = 1 };
+
+// LAYOUT kLrGate: lines are columns (stride ld).  The workgroup owns 8 consecutive columns,
+//   VR = 8 / EPV vectors per row; thread t holds rows t, t + 1024, ...: its vector j is vector
+//   j % VR of row t + (j / VR) 1024, and element e of it is on line (j % VR) EPV + e.
+//   Workgroups are numbered so that the 8 that share 64 consecutive columns (the same 128-byte
+//   pieces of every row) run on the same XCD at the same time and meet in its L2.
+// LAYOUT kLrDown: lines are rows (contiguous).  The workgroup owns 8 >> vpl_log2 ... 8 consecutive
+//   rows; a thread holds 1 << vpl_log2 vectors of each: its vector j is vector
+//   t + (j & (vpl - 1)) 1024 of line j >> vpl_log2.
+// FACTOR_ALONG: the factor varies along the line (the DaSS configuration, Eq. 4 / Eq. 5) and
+//   the scaled factors of all positions are staged in LDS; otherwise there is one per line.
+// The host guarantees 0 < n_keep < line length.
+template <int DT, int LAYOUT, bool FACTOR_ALONG>
+__global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
+    void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
+    int fmode, uint32_t n_keep, uint8_t *__restrict__ mask, int vpl_log2, int lines_per_block)
+{
+    constexpr int NT = kLrThreads, VPT = kLrVecs;
+    constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
+    constexpr int EB = DT == DASS_BF16 ? 2 : 4;
+    constexpr int VR = 8 / EPV;
+    constexpr bool GATE = LAYOUT == kLrGate;
+    extern __shared__ __attribute__((aligned(16))) char lr_smem[];
+    uint32_t *hist = reinterpret_cast<uint32_t *>(lr_smem);                           // [kLrLines][kLrBins]
+    LrState *state = reinterpret_cast<LrState *>(lr_smem + kLrLines * kLrBins * 4);   // [kLrLines]
+    uint32_t *flags = reinterpret_cast<uint32_t *>(state + kLrLines);                 // [0] a line is open, [1] f64 form wanted
+    float *fl = reinterpret_cast<float *>(flags + 4);                                 // scaled factors
+
+    const int tid = threadIdx.x;
+    const int64_t len = GATE ? rows : cols;
+    char *W = static_cast<char *>(Wv);
+    // Gate: blockIdx -> column octet (see above); the grid is padded to a multiple of 64
+    const uint32_t slot = blockIdx.x / 8;
+    const int64_t octet = GATE ? (int64_t)((slot / 8) * 8 + blockIdx.x % 8) * 8 + slot % 8 : 0;
+    if (GATE && octet >= cols / 8)
+        return;
+    const int64_t c0 = octet * 8;
+    const int64_t row0 = GATE ? 0 : (int64_t)blockIdx.x * lines_per_block;
+    const int n_lines = GATE ? 8 : (int)(rows - row0 < lines_per_block ? rows - row0 : lines_per_block);
+    const int64_t vec_per_line = cols / EPV;   // Down
+    const int vpl_mask = (1 << vpl_log2) - 1;
+
+    auto vec_line0 = [&](int j) { return GATE ? (j % VR) * EPV : j >> vpl_log2; };   // line of its element 0
+    // A thread recomputes what depends on its number in every phase from a fresh copy of it
+    // (t below), so that no per-vector address or flag occupies a register across the phases.
+    auto fresh_tid = [&]() {
+        uint32_t x = (uint32_t)tid;
+        asm volatile("" : "+v"(x));
+        return x;
+    };
+    // position of vector j along the lines: Gate: its row; Down: its index inside the line
+    auto vec_pos = [&](int j, uint32_t t) -> uint32_t {
+        return GATE ? t + (uint32_t)(j / VR) * NT : t + (uint32_t)(j & vpl_mask) * NT;
+    };
+    auto vec_valid = [&](int j, uint32_t t) {
+        return GATE ? vec_pos(j, t) < (uint32_t)rows
+                    : (vec_line0(j) < n_lines && vec_pos(j, t) < (uint32_t)vec_per_line);
+    };
+    // byte offsets fit 32 bits (checked by the host)
+    const uint32_t ld32 = (uint32_t)ld, col_bytes = (uint32_t)c0 * EB, row0_32 = (uint32_t)row0;
+    auto vec_addr = [&](int j, uint32_t t) -> char * {
+        if (GATE)
+            return W + (size_t)(vec_pos(j, t) * ld32 * EB + col_bytes + (uint32_t)((j % VR) * EPV * EB));
+        return W + (size_t)((row0_32 + (uint32_t)vec_line0(j)) * ld32 * EB + vec_pos(j, t) * (EPV * EB));
+    };
+
+    u32x4 v[VPT];
+    {
+        const uint32_t t = fresh_tid();
+#pragma unroll
+        for (int j = 0; j < VPT; ++j)
+            if (vec_valid(j, t))
+                v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vec_addr(j, t)));
+    }
+
+    // ---- factors, scaled as select.h wants them
+    bool fast_ok = true;
+    if constexpr (FACTOR_ALONG) {
+        for (int64_t i = tid; i < len; i += NT) {
+            const float f = factor_of(norms[i], fmode);
+            fast_ok &= factor_in_fast_range(f);
+            fl[i] = f * kFactorScale;
+        }
+    } else {
+        if (tid < n_lines) {   // one per line
+            const float f = factor_of(norms[GATE ? c0 + tid : row0 + tid], fmode);
+            fast_ok &= factor_in_fast_range(f);
+            fl[tid] = f * kFactorScale;
+        }
+    }
+    auto reset_state = [&]() {
+        if (tid < kLrLines) {
+            LrState st;
+            st.a = st.b = st.c = 0;
+            st.need = n_keep;
+            st.open = tid < n_lines ? 1u : 0u;
+            state[tid] = st;
+        }
+    };
+    reset_state();
+    if (tid == 0)
+        flags[1] = 0;
+    __syncthreads();
+    if (!fast_ok)
+        flags[1] = 1;
+    __syncthreads();
+    bool exact = flags[1] != 0;
+
+    // Scaled factors of the EPV elements of vector j (line0: the line of element 0).
+    auto vec_factors = [&](int j, uint32_t t, int line0, float *fs) __attribute__((always_inline)) {
+        if constexpr (FACTOR_ALONG && GATE) {
+            const float f = fl[vec_pos(j, t)];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                fs[e] = f;
+        } else if constexpr (FACTOR_ALONG) {
+#pragma unroll
+            for (int q = 0; q < EPV / 4; ++q) {
+                const u32x4 x = *reinterpret_cast<const u32x4 *>(fl + vec_pos(j, t) * EPV + 4 * q);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    fs[4 * q + i] = __uint_as_float(x[i]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                fs[e] = fl[GATE ? line0 + e : line0];
+        }
+    };
+    auto norm_index = [&](int j, uint32_t t, int e, int line) -> int64_t {
+        if (FACTOR_ALONG)
+            return GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+        return GATE ? c0 + line : row0 + line;
+    };
+
+    // Counting pass on a digit of field A in the two-term form, every vector's code laid out
+    // (the common passes): candidates are the elements whose bits under himask agree with the
+    // decided ones.
+    auto count_fast = [&](int shift, uint32_t wmask, uint32_t himask) __attribute__((always_inline)) {
+        const uint32_t t = fresh_tid();
+        uint32_t sa[kLrLines], open_bits = 0;
+        if constexpr (GATE) {
+#pragma unroll
+            for (int l = 0; l < kLrLines; ++l) {
+                sa[l] = lr_uniform(state[l].a);
+                open_bits |= lr_uniform(state[l].open) << l;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            const int line0 = vec_line0(j);
+            uint32_t da = 0;
+            bool line_open = true;
+            if constexpr (!GATE) {
+                line_open = line0 < n_lines && lr_uniform(state[line0 & (kLrLines - 1)].open) != 0;
+                da = lr_uniform(state[line0 & (kLrLines - 1)].a);
+            }
+            if (line_open && vec_valid(j, t)) {
+                asm volatile("" : "+v"(v[j]));   // nothing derived from the data is carried from pass to pass
+                float fs[EPV];
+                vec_factors(j, t, line0, fs);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int line = GATE ? line0 + e : line0;
+                    if (GATE && !((open_bits >> line) & 1u))
+                        continue;   // uniform
+                    const uint32_t a = __float_as_uint(fabsf(elem_of<DT>(v[j], e)) * fs[e]);
+                    if ((((a ^ (GATE ? sa[line] : da)) & himask) == 0))
+                        atomicAdd(hist + line * kLrBins + ((a >> shift) & wmask), 1u);
+                }
+            }
+        }
+    };
+
+    // Fields A and B of one element, either form.
+    auto fields = [&](float w, float fs, int64_t in, bool need_b, uint32_t &a, uint32_t &b) __attribute__((always_inline)) {
+        w = fabsf(w);
+        if (!exact) {
+            const float p = w * fs;
+            a = __float_as_uint(p);
+            b = need_b ? lr_mono(fmaf(w, fs, -p)) : 0u;
+        } else {   // f64 product with the unscaled factor, recomputed from the norm
+            const uint64_t k = (uint64_t)__double_as_longlong((double)w * (double)factor_of(norms[in], fmode));
+            a = (uint32_t)(k >> 32);
+            b = (uint32_t)k;
+        }
+    };
+    // The rare passes (fields B and C, f64 form) go through one copy of the code: the loop
+    // handles the vector in v[0] and rotates the array, so that after VPT turns it is back in place.
+    auto rotate = [&]() __attribute__((always_inline)) {
+        const u32x4 first = v[0];
+#pragma unroll
+        for (int i = 0; i + 1 < VPT; ++i)
+            v[i] = v[i + 1];
+        v[VPT - 1] = first;
+    };
+    auto count_any = [&](const LrPass ps, uint32_t wmask, uint32_t himask) __attribute__((always_inline)) {
+        const uint32_t t = fresh_tid();
+#pragma clang loop unroll(disable)
+        for (int j = 0; j < VPT; ++j) {
+            const int line0 = vec_line0(j);
+            if (vec_valid(j, t)) {
+                float fs[EPV];
+                vec_factors(j, t, line0, fs);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int line = GATE ? line0 + e : line0;
+                    const LrState st = state[line];
+                    const int64_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+                    uint32_t a, b;
+                    fields(elem_of<DT>(v[0], e), fs[e], norm_index(j, t, e, line), true, a, b);
+                    const uint32_t c = 0xFFFFu - (uint32_t)idx;
+                    bool cand = st.open != 0;
+                    uint32_t x;
+                    if (ps.field == 0) {
+                        cand = cand && ((a ^ st.a) & himask) == 0;
+                        x = a;
+                    } else if (ps.field == 1) {
+                        cand = cand && a == st.a && ((b ^ st.b) & himask) == 0;
+                        x = b;
+                    } else {
+                        cand = cand && a == st.a && b == st.b && ((c ^ st.c) & himask) == 0;
+                        x = c;
+                    }
+                    if (cand)
+                        atomicAdd(hist + line * kLrBins + ((x >> ps.shift) & wmask), 1u);
+                }
+            }
+            rotate();
+        }
+    };
+
+    for (int pass = 0;; ++pass) {
+        for (int i = tid; i < kLrLines * kLrBins / 4; i += NT)
+            reinterpret_cast<u32x4 *>(hist)[i] = u32x4{0, 0, 0, 0};
+        if (tid == 0)
+            flags[0] = 0;
+        __syncthreads();
+        const LrPass ps = lr_pass(pass);
+        const uint32_t wmask = (1u << ps.width) - 1u;
+        const uint32_t himask = ps.shift + ps.width >= 32 ? 0u : ~0u << (ps.shift + ps.width);
+        if (ps.field == 0 && !exact)
+            count_fast(ps.shift, wmask, himask);
+        else
+            count_any(ps, wmask, himask);
+        __syncthreads();
+        // wavefront l settles line l; a product that became infinite shows in the first digit of p
+        const int wave = tid / 64;
+        if (wave < n_lines && state[wave].open) {   // uniform inside the wavefront
+            const uint32_t alarm_bin = (!exact && pass == 0) ? (0x7f800000u >> 21) : (uint32_t)kLrBins;
+            const bool alarm = lr_settle(hist + wave * kLrBins, state + wave, ps, pass, alarm_bin);
+            if ((tid & 63) == 0) {
+                if (state[wave].open)
+                    flags[0] = 1;
+                if (alarm)
+                    flags[1] = 1;
+            }
+        }
+        __syncthreads();
+        if (!exact && flags[1]) {   // start again on f64 products (uniform)
+            exact = true;
+            reset_state();
+            pass = -1;
+            __syncthreads();
+            continue;
+        }
+        if (!flags[0])
+            break;   // uniform
+        __syncthreads();   // flags[0] is cleared at the top of the next pass
+    }
+
+    // ---- apply: zero what ranks below the threshold, store, write the mask bits
+    bool beyond_a = false;   // a threshold decided beyond field A
+    for (int l = 0; l < n_lines; ++l)
+        beyond_a |= state[l].b != 0 || state[l].c != 0;
+    beyond_a = lr_uniform(beyond_a) != 0;
+
+    auto write_mask = [&](int j, uint32_t t, int line0, uint32_t kept, uint32_t &row_bits) __attribute__((always_inline)) {
+        if (!mask)
+            return;
+        if constexpr (GATE) {   // with f32 the first vector's keep bits wait for the second one's
+            row_bits |= kept << ((j % VR) * EPV);
+            if (j % VR == VR - 1) {
+                mask[(int64_t)vec_pos(j, t) * (cols / 8) + octet] = (uint8_t)row_bits;
+                row_bits = 0;
+            }
+        } else {
+            const int64_t r = row0 + line0;
+            if constexpr (EPV == 8)
+                mask[r * (cols / 8) + vec_pos(j, t)] = (uint8_t)kept;
+            else if ((tid & 1) == 0)   // see the caller: row_bits holds the neighbouring lane's half
+                mask[r * (cols / 8) + vec_pos(j, t) / 2] = (uint8_t)(kept | (row_bits << 4));
+        }
+    };
+
+    const uint32_t t = fresh_tid();
+    if (!exact && !beyond_a) {   // keep iff A >= the threshold's A
+        uint32_t sa[kLrLines];
+        if constexpr (GATE) {
+#pragma unroll
+            for (int l = 0; l < kLrLines; ++l)
+                sa[l] = lr_uniform(state[l].a);
+        }
+        uint32_t row_bits = 0;
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            const int line0 = vec_line0(j);
+            const bool valid = vec_valid(j, t);
+            uint32_t kept = 0;
+            if (valid) {
+                const uint32_t da = GATE ? 0u : lr_uniform(state[line0 & (kLrLines - 1)].a);
+                float fs[EPV];
+                vec_factors(j, t, line0, fs);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const uint32_t a = __float_as_uint(fabsf(elem_of<DT>(v[j], e)) * fs[e]);
+                    const bool keep = a >= (GATE ? sa[line0 + e] : da);
+                    zero_lane_if<DT>(v[j], e, !keep);
+                    kept |= (keep ? 1u : 0u) << e;
+                }
+                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4 *>(vec_addr(j, t)));
+            }
+            if (!GATE && EPV == 4)
+                row_bits = __shfl_xor(kept, 1, 64);
+            if (valid)
+                write_mask(j, t, line0, kept, row_bits);
+        }
+    } else {
+        uint32_t row_bits = 0;
+#pragma clang loop unroll(disable)
+        for (int j = 0; j < VPT; ++j) {
+            const int line0 = vec_line0(j);
+            const bool valid = vec_valid(j, t);
+            uint32_t kept = 0;
+            if (valid) {
+                float fs[EPV];
+                vec_factors(j, t, line0, fs);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int line = GATE ? line0 + e : line0;
+                    const int64_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+                    uint32_t a, b;
+                    fields(elem_of<DT>(v[0], e), fs[e], norm_index(j, t, e, line), true, a, b);
+                    const bool keep = lr_keep(state[line], a, b, 0xFFFFu - (uint32_t)idx);
+                    zero_lane_if<DT>(v[0], e, !keep);
+                    kept |= (keep ? 1u : 0u) << e;
+                }
+                __builtin_nontemporal_store(v[0], reinterpret_cast<u32x4 *>(vec_addr(j, t)));
+            }
+            if (!GATE && EPV == 4)
+                row_bits = __shfl_xor(kept, 1, 64);
+            if (valid)
+                write_mask(j, t, line0, kept, row_bits);
+            rotate();
+        }
+    }
+}
+
 }  // namespace dass
 
 extern "C" size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, dass_dtype dt,
@@ -450,13 +933,61 @@ extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64
         return fail(DASS_ERR_SHAPE, "%s: too many lines for one launch", fn);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint32_t n_keep = (uint32_t)(len - n_prune);
+    const bool bf16 = dt == DASS_BF16;
+
+    // Lines that fit the registers of one workgroup, exponent with an exact f32 factor: the
+    // weights are read once.
+    if ((alpha == 0.0 || alpha == 0.5 || alpha == 1.0) && len <= 0xFFFF && n_keep > 0 && n_keep < (uint32_t)len) {
+        const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
+        const bool along = norm_axis == group_axis;
+        const bool gate = group_axis == DASS_AXIS_ROWS;
+        const int epv = vec_elems(dt);
+        bool fits;
+        int vpl_log2 = 0, lpb = kLrLines;
+        int64_t grid;
+        if (gate) {   // a thread holds 8 / epv vectors of every 1024th row
+            fits = (rows + kLrThreads - 1) / kLrThreads * (8 / epv) <= kLrVecs;
+            grid = (cols / 8 + 63) / 64 * 64;
+        } else {      // a thread holds 2^vpl_log2 vectors of each of its workgroup's lines
+            const int64_t vpl = (cols / epv + kLrThreads - 1) / kLrThreads;
+            while ((1 << vpl_log2) < vpl && vpl_log2 < 5)
+                ++vpl_log2;
+            fits = (1 << vpl_log2) <= kLrVecs;
+            if (fits && kLrVecs >> vpl_log2 < lpb)
+                lpb = kLrVecs >> vpl_log2;
+            grid = (rows + lpb - 1) / lpb;
+        }
+        const size_t smem = (size_t)kLrLines * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 +
+                            (along ? (size_t)len : (size_t)kLrLines) * sizeof(float);
+        if (fits && grid <= 0x7fffffffLL && smem <= 160 * 1024 && rows * ld * (bf16 ? 2 : 4) < (1LL << 32)) {
+            using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int,
+                                 int);
+            k_t k;
+            if (bf16)
+                k = gate ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
+                                  : unstructured_resident_kernel<DASS_BF16, kLrGate, false>)
+                         : (along ? unstructured_resident_kernel<DASS_BF16, kLrDown, true>
+                                  : unstructured_resident_kernel<DASS_BF16, kLrDown, false>);
+            else
+                k = gate ? (along ? unstructured_resident_kernel<DASS_F32, kLrGate, true>
+                                  : unstructured_resident_kernel<DASS_F32, kLrGate, false>)
+                         : (along ? unstructured_resident_kernel<DASS_F32, kLrDown, true>
+                                  : unstructured_resident_kernel<DASS_F32, kLrDown, false>);
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)smem) != hipSuccess)
+                return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, smem);
+            hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kLrThreads), smem, stream, W, rows, cols, ld, norms,
+                               fmode, n_keep, mask_out, vpl_log2, lpb);
+            return check_launch("unstructured kernel");
+        }
+    }
+
     float *f = static_cast<float *>(workspace);
     s = launch_factor(norms, norm_axis == DASS_AXIS_ROWS ? rows : cols, alpha, f, stream);
     if (s != DASS_OK)
         return s;
 
-    const uint32_t n_keep = (uint32_t)(len - n_prune);
-    const bool bf16 = dt == DASS_BF16;
     const dim3 grid((unsigned)blocks), block(kUBlock);
     if (group_axis == DASS_AXIS_COLS) {
         auto k = bf16 ? (norm_axis == DASS_AXIS_COLS ? unstructured_cols_kernel<DASS_BF16, true>

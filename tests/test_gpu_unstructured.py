@@ -84,6 +84,60 @@ def test_unstructured_magnitude_ties_on_long_lines(gpu_device, dtype):
     assert bits_equal(W, want), first_mismatch(W, want)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols"), ("rows", "cols")])
+def test_unstructured_extreme_magnitudes(gpu_device, dtype, axes):
+    """Scores near the bottom and the top of the f32 range (subnormal weights, tiny and huge norms,
+    products that underflow or overflow in f32) and exact zeros: the selection must stay exact."""
+    rows, cols = 200, 256
+    g = torch.Generator(device="cpu").manual_seed(78)
+    mant = torch.rand((rows, cols), generator=g) + 1.0
+    expo = torch.randint(-140, -100, (rows, cols), generator=g).to(torch.float32)
+    W = (mant * torch.exp2(expo)).to(dtype)                       # tiny, partly subnormal
+    W[::3] = (mant[::3] * torch.exp2(expo[::3] + 225.0)).to(dtype)  # huge
+    W[:, ::5] = 0.0
+    W = W * torch.where(torch.rand((rows, cols), generator=g) < 0.5, -1.0, 1.0).to(dtype)
+    n = rows if axes[0] == "rows" else cols
+    length = rows if axes[1] == "rows" else cols
+    nrm = torch.exp2(torch.randint(-60, 60, (n,), generator=g).to(torch.float32)) * \
+        (torch.rand(n, generator=g) + 1.0)
+    nrm[::7] = 0.0
+    W, nrm = W.to(gpu_device), nrm.to(torch.float32).to(gpu_device)
+    for alpha, n_prune in ((0.5, length // 2), (1.0, length // 3)):
+        Wc = W.clone()
+        want, want_mask = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), axes[0], axes[1], alpha,
+                                                   n_prune, want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(Wc, nrm, axes[0], axes[1], alpha, n_prune, mask_out=mask)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), first_mismatch(Wc, want)
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+def test_unstructured_scores_equal_to_f32_precision(gpu_device, axes):
+    """Position k of a line has weight 1 + (k mod 64)/128 and norm fl32(P / weight): all products
+    are P up to an f32 rounding error, so their leading f32 terms tie in large numbers and the
+    exact remainders (then the indices) must rank them like the oracle."""
+    length, lines = 1536, 40
+    g = torch.Generator(device="cpu").manual_seed(11)
+    k = torch.arange(length) % 64
+    k = k[torch.randperm(length, generator=g)]
+    w_line = 1.0 + k.to(torch.float64) / 128.0                    # exact in bf16
+    nrm = (3.7 / w_line).to(torch.float32)
+    sign = torch.where(torch.rand((lines, length), generator=g) < 0.5, -1.0, 1.0).to(torch.float64)
+    W = (sign * w_line).to(torch.bfloat16)                        # lines are rows here
+    if axes[1] == "rows":
+        W = W.t().contiguous()
+    W, nrm = W.to(gpu_device), nrm.to(gpu_device)
+    for n_prune in (length // 2, 5, length - 3):
+        Wc = W.clone()
+        want, _ = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), axes[0], axes[1], 1.0, n_prune)
+        dass.score_mask_unstructured(Wc, nrm, axes[0], axes[1], 1.0, n_prune)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), first_mismatch(Wc, want)
+
+
 def test_unstructured_leading_dimension(gpu_device):
     _run_case(gpu_device, 100, 104, torch.bfloat16, ("cols", "cols"), 1.0, 52, seed=7, pad=24)
     _run_case(gpu_device, 100, 104, torch.float32, ("rows", "rows"), 0.5, 50, seed=8, pad=12)
