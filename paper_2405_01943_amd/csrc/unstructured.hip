@@ -437,6 +437,7 @@ constexpr int kLrLines = 8;
 constexpr int kLrPasses = 8;
 constexpr int kLrThreads = 1024;
 constexpr int kLrVecs = 16;   // 16-byte vectors held by a thread
+constexpr int kLrTies = 64;   // scores equal in field A around the threshold that are ranked directly, per line
 
 struct LrState {
     uint32_t a, b, c;   // decided digits of the threshold, undecided bits 0
@@ -561,7 +562,10 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     uint32_t *hist = reinterpret_cast<uint32_t *>(lr_smem);                           // [kLrLines][kLrBins]
     LrState *state = reinterpret_cast<LrState *>(lr_smem + kLrLines * kLrBins * 4);   // [kLrLines]
     uint32_t *flags = reinterpret_cast<uint32_t *>(state + kLrLines);                 // [0] a line is open, [1] f64 form wanted
-    float *fl = reinterpret_cast<float *>(flags + 4);                                 // scaled factors
+    uint32_t *trash = flags + 4;                                                      // [64] counters nobody reads
+    uint32_t *tie_count = trash + 64;                                                 // [kLrLines]
+    uint2 *tie_list = reinterpret_cast<uint2 *>(tie_count + kLrLines);                // [kLrLines][kLrTies] fields (B, C)
+    float *fl = reinterpret_cast<float *>(tie_list + kLrLines * kLrTies);             // scaled factors
 
     const int tid = threadIdx.x;
     const int64_t len = GATE ? rows : cols;
@@ -632,6 +636,7 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             st.need = n_keep;
             st.open = tid < n_lines ? 1u : 0u;
             state[tid] = st;
+            tie_count[tid] = 0;
         }
     };
     reset_state();
@@ -675,12 +680,17 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     // decided ones.
     auto count_fast = [&](int shift, uint32_t wmask, uint32_t himask) __attribute__((always_inline)) {
         const uint32_t t = fresh_tid();
-        uint32_t sa[kLrLines], open_bits = 0;
+        // Straight-line code per element (a branch per element would make every LDS access wait
+        // for the one before): an element that is no candidate adds to a per-lane dummy counter.
+        // A closed line gets a pattern no score matches (scores have the sign bit clear).
+        uint32_t *const dummy = trash + (t & 63u);
+        uint32_t sa[kLrLines], hm[kLrLines];
         if constexpr (GATE) {
 #pragma unroll
             for (int l = 0; l < kLrLines; ++l) {
-                sa[l] = lr_uniform(state[l].a);
-                open_bits |= lr_uniform(state[l].open) << l;
+                const bool open = lr_uniform(state[l].open) != 0;
+                sa[l] = open ? lr_uniform(state[l].a) : 0xFFFFFFFFu;
+                hm[l] = open ? himask : 0xFFFFFFFFu;
             }
         }
 #pragma unroll
@@ -700,13 +710,71 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) {
                     const int line = GATE ? line0 + e : line0;
-                    if (GATE && !((open_bits >> line) & 1u))
-                        continue;   // uniform
                     const uint32_t a = __float_as_uint(fabsf(elem_of<DT>(v[j], e)) * fs[e]);
-                    if ((((a ^ (GATE ? sa[line] : da)) & himask) == 0))
-                        atomicAdd(hist + line * kLrBins + ((a >> shift) & wmask), 1u);
+                    const bool cand = ((a ^ (GATE ? sa[line] : da)) & (GATE ? hm[line] : himask)) == 0;
+                    atomicAdd(cand ? hist + line * kLrBins + ((a >> shift) & wmask) : dummy, 1u);
                 }
             }
+        }
+    };
+
+    // After the three passes on field A a line is still open only when several scores share the
+    // threshold's A.  They are few: each goes into the line's list as (B, C), and one wavefront
+    // ranks them directly (a list that overflows leaves the line to the digit passes on B and C).
+    auto collect_ties = [&]() __attribute__((always_inline)) {
+        const uint32_t t = fresh_tid();
+        uint32_t sa[kLrLines];
+        if constexpr (GATE) {
+#pragma unroll
+            for (int l = 0; l < kLrLines; ++l)   // a closed line gets a pattern no score has
+                sa[l] = lr_uniform(state[l].open) != 0 ? lr_uniform(state[l].a) : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            const int line0 = vec_line0(j);
+            uint32_t da = 0;
+            bool line_open = true;
+            if constexpr (!GATE) {
+                line_open = line0 < n_lines && lr_uniform(state[line0 & (kLrLines - 1)].open) != 0;
+                da = lr_uniform(state[line0 & (kLrLines - 1)].a);
+            }
+            if (line_open && vec_valid(j, t)) {
+                asm volatile("" : "+v"(v[j]));
+                float fs[EPV];
+                vec_factors(j, t, line0, fs);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int line = GATE ? line0 + e : line0;
+                    const float w = fabsf(elem_of<DT>(v[j], e));
+                    const float p = w * fs[e];
+                    if (__float_as_uint(p) == (GATE ? sa[line] : da)) {
+                        const uint32_t slot = atomicAdd(tie_count + line, 1u);
+                        if (slot < (uint32_t)kLrTies) {
+                            const uint32_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+                            tie_list[line * kLrTies + slot] = make_uint2(lr_mono(fmaf(w, fs[e], -p)), 0xFFFFu - idx);
+                        }
+                    }
+                }
+            }
+        }
+    };
+    // Wavefront `line` ranks its line's list and closes the line on the entry of the wanted rank.
+    auto rank_ties = [&](int line) {
+        const uint32_t n = tie_count[line];
+        if (n > (uint32_t)kLrTies)
+            return;
+        const uint32_t lane = tid & 63;
+        const uint2 mine = tie_list[line * kLrTies + (lane < n ? lane : 0)];
+        uint32_t above = 0;
+        for (uint32_t k = 0; k < n; ++k) {
+            const uint2 other = tie_list[line * kLrTies + k];
+            above += (other.x > mine.x) | ((other.x == mine.x) & (other.y > mine.y));
+        }
+        if (lane < n && above + 1 == state[line].need) {   // composites differ, so exactly one lane
+            state[line].b = mine.x;
+            state[line].c = mine.y;
+            state[line].open = 0;
         }
     };
 
@@ -805,6 +873,21 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
         if (!flags[0])
             break;   // uniform
         __syncthreads();   // flags[0] is cleared at the top of the next pass
+        if (pass == 2 && !exact) {   // field A is decided and some line has ties on it
+            collect_ties();
+            __syncthreads();
+            if (wave < n_lines && state[wave].open)   // uniform inside the wavefront
+                rank_ties(wave);
+            if (tid == 0)
+                flags[0] = 0;
+            __syncthreads();
+            if (tid < n_lines && state[tid].open)
+                flags[0] = 1;
+            __syncthreads();
+            if (!flags[0])
+                break;   // uniform
+            __syncthreads();
+        }
     }
 
     // ---- apply: zero what ranks below the threshold, store, write the mask bits
@@ -832,12 +915,18 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     };
 
     const uint32_t t = fresh_tid();
-    if (!exact && !beyond_a) {   // keep iff A >= the threshold's A
-        uint32_t sa[kLrLines];
+    // The common forms, every vector's code laid out: without fields B and C (keep iff A >= the
+    // threshold's A) and with them.
+    auto apply_fast = [&](auto with_bc_tag) __attribute__((always_inline)) {
+        constexpr bool BC = decltype(with_bc_tag)::value;
+        uint32_t sa[kLrLines], sb[kLrLines], sc[kLrLines];
         if constexpr (GATE) {
 #pragma unroll
-            for (int l = 0; l < kLrLines; ++l)
+            for (int l = 0; l < kLrLines; ++l) {
                 sa[l] = lr_uniform(state[l].a);
+                sb[l] = BC ? lr_uniform(state[l].b) : 0u;
+                sc[l] = BC ? lr_uniform(state[l].c) : 0u;
+            }
         }
         uint32_t row_bits = 0;
 #pragma unroll
@@ -847,23 +936,45 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             const bool valid = vec_valid(j, t);
             uint32_t kept = 0;
             if (valid) {
-                const uint32_t da = GATE ? 0u : lr_uniform(state[line0 & (kLrLines - 1)].a);
+                const int l0 = line0 & (kLrLines - 1);
+                const uint32_t da = GATE ? 0u : lr_uniform(state[l0].a);
+                const uint32_t db = GATE || !BC ? 0u : lr_uniform(state[l0].b);
+                const uint32_t dc = GATE || !BC ? 0u : lr_uniform(state[l0].c);
                 float fs[EPV];
                 vec_factors(j, t, line0, fs);
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) {
-                    const uint32_t a = __float_as_uint(fabsf(elem_of<DT>(v[j], e)) * fs[e]);
-                    const bool keep = a >= (GATE ? sa[line0 + e] : da);
+                    const float w = fabsf(elem_of<DT>(v[j], e));
+                    const float p = w * fs[e];
+                    const uint32_t a = __float_as_uint(p);
+                    const uint32_t ta = GATE ? sa[line0 + e] : da;
+                    bool keep;
+                    if constexpr (BC) {
+                        const uint32_t tb = GATE ? sb[line0 + e] : db, tc = GATE ? sc[line0 + e] : dc;
+                        const uint32_t b = lr_mono(fmaf(w, fs[e], -p));
+                        const uint32_t c = 0xFFFFu - (GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e);
+                        keep = (a > ta) | ((a == ta) & ((b > tb) | ((b == tb) & (c >= tc))));
+                    } else {
+                        keep = a >= ta;
+                    }
                     zero_lane_if<DT>(v[j], e, !keep);
                     kept |= (keep ? 1u : 0u) << e;
                 }
-                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4 *>(vec_addr(j, t)));
+                if constexpr (GATE)   // neighbouring workgroups write the other parts of the same 128 bytes: let L2 merge them
+                    *reinterpret_cast<u32x4 *>(vec_addr(j, t)) = v[j];
+                else
+                    __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4 *>(vec_addr(j, t)));
             }
             if (!GATE && EPV == 4)
                 row_bits = __shfl_xor(kept, 1, 64);
             if (valid)
                 write_mask(j, t, line0, kept, row_bits);
         }
+    };
+    if (!exact && !beyond_a) {
+        apply_fast(std::false_type{});
+    } else if (!exact) {
+        apply_fast(std::true_type{});
     } else {
         uint32_t row_bits = 0;
 #pragma clang loop unroll(disable)
@@ -958,7 +1069,8 @@ extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64
                 lpb = kLrVecs >> vpl_log2;
             grid = (rows + lpb - 1) / lpb;
         }
-        const size_t smem = (size_t)kLrLines * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 +
+        const size_t smem = (size_t)kLrLines * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 + 256 +
+                            kLrLines * 4 + kLrLines * kLrTies * 8 +
                             (along ? (size_t)len : (size_t)kLrLines) * sizeof(float);
         if (fits && grid <= 0x7fffffffLL && smem <= 160 * 1024 && rows * ld * (bf16 ? 2 : 4) < (1LL << 32)) {
             using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int,
