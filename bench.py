@@ -40,8 +40,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 MEASURED_TRAFFIC = {
     "stage1": {"sources": ("calib.hip",), "sha256": "254476520601eedef04d1d91f87a1b75efeb38af6fb87f2f5503c5f1d42f65bf",
                "bytes": (34629200 * 2.0 + 88064) * 1024},
-    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "5a9a45c21f96c8ad5177462443b6efebb1bc79ddfe794006a56ac60ccf051398",
-               "bytes": (2 * (44419.6 * 2.0 + 88064.6) + (44533.0 * 2.0 + 88064.6)) * 1024},
+    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "406f4fd2dcd110786fd33d37b51423d8354e7e9a1fad6be88bd10e65dd0e9211",
+               "bytes": (2 * (44419.5 * 2.0 + 88068.2) + (44533.0 * 2.0 + 88078.8)) * 1024},
 }
 
 
