@@ -40,8 +40,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 MEASURED_TRAFFIC = {
     "stage1": {"sources": ("calib.hip",), "sha256": "254476520601eedef04d1d91f87a1b75efeb38af6fb87f2f5503c5f1d42f65bf",
                "bytes": (34629200 * 2.0 + 88064) * 1024},
-    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "406f4fd2dcd110786fd33d37b51423d8354e7e9a1fad6be88bd10e65dd0e9211",
-               "bytes": (2 * (44419.5 * 2.0 + 88068.2) + (44533.0 * 2.0 + 88078.8)) * 1024},
+    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "021c3339f721ba7bacecafc3bc608e59d0edb8307e2673071fa1762e4faa73b7",
+               "bytes": (2 * (44423.5 * 2.0 + 88070.0) + (44526.5 * 2.0 + 88065.0)) * 1024},
 }
 
 
@@ -64,6 +64,8 @@ def parse_args():
     ap.add_argument("--tokens", type=int, default=0, help="override the token count (debugging)")
     ap.add_argument("--nm", default="2:4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--model-layers", type=int, default=32,
+                    help="layers of the whole-model stage-2 measurement (0 skips it)")
     ap.add_argument("--stage2-launches", type=int, default=24)
     return ap.parse_args()
 
@@ -202,6 +204,47 @@ def main():
     s2_gbs = 3 * bytes_per_matrix / (s2_avg * 1e-3) / 1e9
     cold_call_us = (2 * cold["gate"]["median_us"] + cold["down"]["median_us"]) / 3.0
 
+    # ---- stage 2 for a whole model: all layers x (gate, up, down), batched against one call each ----
+    model = None
+    if args.model_layers > 0:
+        L = args.model_layers
+        base = (Wg, Wu, Wd)
+        kinds = (("rows", "rows", cfg.alpha_gate_up), ("rows", "rows", cfg.alpha_gate_up), ("cols", "cols", cfg.alpha_down))
+        layers = [[w.clone() for w in base] for _ in range(L)]      # > 256 MB from 2 layers on: HBM-honest
+        tasks = [(layers[l][k], norms, kinds[k][0], kinds[k][1], kinds[k][2]) for l in range(L) for k in range(3)]
+        ws_model = torch.empty(max(16, dass.nm_batched_workspace_bytes(tasks)), dtype=torch.uint8, device=dev)
+
+        def restore():
+            for lay in layers:
+                for w, w0 in zip(lay, base):
+                    w.copy_(w0)
+
+        def timed(fn):
+            ts = []
+            for _ in range(4):
+                restore()
+                a, b = ev(), ev()
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return statistics.median(ts[1:])
+
+        def one_by_one():
+            for w, n, na, ga, al in tasks:
+                dass.score_mask_nm(w, n, na, ga, al, n_keep, m, workspace=ws_model)
+
+        ms_batched = timed(lambda: dass.score_mask_nm_batched(tasks, n_keep, m, workspace=ws_model))
+        ms_single = timed(one_by_one)
+        model_bytes = 3 * L * bytes_per_matrix
+        model = {"layers": L, "matrices": 3 * L, "bytes": model_bytes,
+                 "batched_ms": ms_batched, "batched_GBps": model_bytes / (ms_batched * 1e-3) / 1e9,
+                 "batched_frac_of_hbm_peak": model_bytes / (ms_batched * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                 "one_call_per_matrix_ms": ms_single,
+                 "one_call_per_matrix_GBps": model_bytes / (ms_single * 1e-3) / 1e9}
+        del layers, tasks
+
     out = {
         "metric": "calib tokens/s (fused GLU-norm, %MFMA peak) + N:M mask GB/s, LLaMA2-7B MLP",
         "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -225,6 +268,8 @@ def main():
                    "cold_single_launch_GBps": bytes_per_matrix / (cold_call_us * 1e-6) / 1e9,
                    "bytes_per_matrix": bytes_per_matrix},
     }
+    if model is not None:
+        out["stage2_whole_model"] = model
     if not args.no_cpu_baseline:
         n_sample = min(T, 2048)
         out["cpu_baseline"] = cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X[:n_sample],

@@ -129,6 +129,38 @@ dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, int64_t ld, 
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Stage 2 for many matrices at once: the N:M masks of all MLP matrices of a
+ * model (Sec. 4.5 times the pruning of a whole model; its layers are
+ * independent, Sec. 3).  Every task is what one dass_score_mask_nm() call
+ * would do, with n_keep:m and dt common to all tasks; the result is the same
+ * bit for bit.  Tasks of equal shape, axes and exponent that take the one-pass
+ * path (2 n_keep = m <= 8, alpha in {0, 0.5, 1}) share kernel launches, up to
+ * 96 matrices per launch, so no launch gap separates their ~30 us of work;
+ * any other task is run as a call of its own, in the order given.
+ *
+ *   tasks      HOST array of n_tasks descriptors (read before the call
+ *              returns); W, norms, mask_out are DEVICE pointers as in
+ *              dass_score_mask_nm().  The matrices must not overlap.
+ *   workspace  device scratch of at least dass_nm_batched_workspace_bytes()
+ *              bytes (the largest single-task need), 16-byte aligned.
+ *   On an invalid task nothing is launched and the error names its index.
+ */
+typedef struct {
+    void *W;
+    int64_t rows, cols, ld;
+    const float *norms;
+    dass_axis norm_axis, group_axis;
+    double alpha;
+    uint8_t *mask_out; /* NULL or rows * (cols / 8) bytes */
+} dass_nm_task;
+
+size_t dass_nm_batched_workspace_bytes(const dass_nm_task *tasks, int64_t n_tasks);
+
+dass_status dass_score_mask_nm_batched(const dass_nm_task *tasks, int64_t n_tasks, dass_dtype dt,
+                                       int n_keep, int m, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream);
+
+/*
  * Stage 2 -- DaSS scoring with per-line unstructured selection (Sec. 3
  * "Pruning Granularity": weights are compared for each input individually for
  * Gate/Up, for each output individually for Down, and the lowest scores of

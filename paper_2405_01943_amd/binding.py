@@ -23,9 +23,17 @@ AXIS = {"rows": 0, "cols": 1}
 EXPORTS = (
     "dass_calib_workspace_bytes", "dass_calib_norms",
     "dass_nm_workspace_bytes", "dass_score_mask_nm",
+    "dass_nm_batched_workspace_bytes", "dass_score_mask_nm_batched",
     "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
     "dass_status_string", "dass_last_error_string", "dass_version",
 )
+
+
+class NmTask(ctypes.Structure):
+    """dass_nm_task of include/dass.h."""
+    _fields_ = [("W", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("norms", ctypes.c_void_p), ("norm_axis", ctypes.c_int),
+                ("group_axis", ctypes.c_int), ("alpha", ctypes.c_double), ("mask_out", ctypes.c_void_p)]
 
 
 class DassError(RuntimeError):
@@ -65,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.dass_score_mask_nm.restype = ci
     lib.dass_score_mask_nm.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, ci, ci, vp,
                                        vp, sz, vp]
+    lib.dass_nm_batched_workspace_bytes.restype = sz
+    lib.dass_nm_batched_workspace_bytes.argtypes = [ctypes.POINTER(NmTask), i64]
+    lib.dass_score_mask_nm_batched.restype = ci
+    lib.dass_score_mask_nm_batched.argtypes = [ctypes.POINTER(NmTask), i64, ci, ci, ci, vp, sz, vp]
     lib.dass_unstructured_workspace_bytes.restype = sz
     lib.dass_unstructured_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
     lib.dass_score_mask_unstructured.restype = ci
@@ -167,6 +179,52 @@ def score_mask_nm(W: torch.Tensor, norms: torch.Tensor, norm_axis: str, group_ax
                                   AXIS[norm_axis], AXIS[group_axis], float(alpha), int(n_keep),
                                   int(m), _ptr(mask_out), _ptr(workspace), ws_bytes,
                                   _stream(stream)))
+
+
+def _nm_task_array(tasks):
+    """tasks: sequence of (W, norms, norm_axis, group_axis, alpha[, mask_out]) -> (NmTask array, dtype, device)."""
+    arr = (NmTask * max(len(tasks), 1))()
+    dtype = device = None
+    for i, t in enumerate(tasks):
+        W, norms, norm_axis, group_axis, alpha = t[:5]
+        mask_out = t[5] if len(t) > 5 else None
+        rows, cols, ld = _matrix(W, f"tasks[{i}].W")
+        if dtype is None:
+            dtype, device = W.dtype, W.device
+        elif W.dtype != dtype:
+            raise TypeError("all matrices of a batched call must share one dtype")
+        if norms.dtype != torch.float32 or not norms.is_contiguous():
+            raise TypeError(f"tasks[{i}].norms: need contiguous float32")
+        if norms.numel() != (rows if norm_axis == "rows" else cols):
+            raise ValueError(f"tasks[{i}]: norms length does not match norm_axis")
+        if mask_out is not None and (mask_out.dtype != torch.uint8 or not mask_out.is_contiguous()
+                                     or mask_out.numel() != rows * (cols // 8)):
+            raise TypeError(f"tasks[{i}].mask_out: need contiguous uint8[rows * cols / 8]")
+        arr[i] = NmTask(W.data_ptr(), rows, cols, ld, norms.data_ptr(), AXIS[norm_axis], AXIS[group_axis],
+                        float(alpha), None if mask_out is None else mask_out.data_ptr())
+    return arr, dtype, device
+
+
+def nm_batched_workspace_bytes(tasks) -> int:
+    arr, _, _ = _nm_task_array(tasks)
+    return int(load_library().dass_nm_batched_workspace_bytes(arr, len(tasks)))
+
+
+def score_mask_nm_batched(tasks, n_keep: int, m: int, workspace: Optional[torch.Tensor] = None,
+                          stream=None) -> None:
+    """dass_score_mask_nm_batched: score_mask_nm over many matrices, equal ones sharing launches.
+
+    tasks: sequence of (W, norms, norm_axis, group_axis, alpha[, mask_out]).
+    """
+    lib = load_library()
+    if len(tasks) == 0:
+        return
+    arr, dtype, device = _nm_task_array(tasks)
+    if workspace is None:
+        workspace = _scratch(int(lib.dass_nm_batched_workspace_bytes(arr, len(tasks))), device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.dass_score_mask_nm_batched(arr, len(tasks), DTYPE[dtype], int(n_keep), int(m),
+                                          _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def unstructured_workspace_bytes(rows: int, cols: int, dtype: torch.dtype, norm_axis: str,

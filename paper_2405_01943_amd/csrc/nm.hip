@@ -16,6 +16,9 @@
 //               scores as f64 products, selection by counting wins per lane.
 #include "select.h"
 
+#include <cstdio>
+#include <vector>
+
 #include <type_traits>
 
 #include <mutex>
@@ -89,16 +92,17 @@ __device__ __forceinline__ void zero_at(char *W, int64_t r, int64_t c, int64_t l
 // workgroup covers up to 256 such column slots, so rows are read and written in contiguous
 // pieces of up to 4 KB; every thread makes one pass and the grid covers the matrix (many small workgroups
 // keep HBM busier than a resident grid that loops).
+// (`bid`: the workgroup's number inside this matrix.)
 template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool OPTIMISTIC>
-__global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
+__device__ __forceinline__ void nm_half_rows_body(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
-    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx, uint32_t bid)
 {
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int GB = M >= 4 ? 1 : 2;   // row groups per thread
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
 
-    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;   // 32-bit division
+    const int64_t bx = bid % nbx, by = bid / nbx;   // 32-bit division
     const int64_t slot = bx * blockDim.x + threadIdx.x;
     // Lanes past the last column slot leave.  (With f32 two neighbouring lanes share a mask byte
     // and exchange their halves at the end; cols is a multiple of 8, so they leave or stay together.)
@@ -232,9 +236,9 @@ __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
 // consecutive columns of NV 16-byte vectors and RB rows, RB * UW / M groups; the factors of
 // its columns are computed once.
 template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool OPTIMISTIC>
-__global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
+__device__ __forceinline__ void nm_half_cols_body(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
-    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx, uint32_t bid)
 {
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int UW = M > EPV ? M : EPV;
@@ -243,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
     constexpr int GPR = UW / M;   // groups per row
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
 
-    const int64_t bx = blockIdx.x % nbx, by = blockIdx.x / nbx;   // 32-bit division
+    const int64_t bx = bid % nbx, by = bid / nbx;   // 32-bit division
     const int64_t slot = bx * blockDim.x + threadIdx.x;
     // Lanes past the last column slot read column 0 and write nothing.  (Measured: letting them
     // leave early instead makes this kernel slower.)
@@ -381,6 +385,48 @@ __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
 // ===========================================================================
 // General path: any (n_keep, m, alpha)
 // ===========================================================================
+
+// One matrix per launch.
+template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool OPTIMISTIC>
+__global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
+    void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
+{
+    nm_half_rows_body<DT, M, NORM_ROWS, WITH_MASK, OPTIMISTIC>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
+                                                               blockIdx.x);
+}
+template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool OPTIMISTIC>
+__global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
+    void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
+    int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
+{
+    nm_half_cols_body<DT, M, NORM_COLS, WITH_MASK, OPTIMISTIC>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
+                                                               blockIdx.x);
+}
+
+// Many matrices of one shape per launch (the layers of a model): the table travels in the
+// kernel arguments, a workgroup finds its matrix by one division.  The launch gaps that separate
+// single-matrix kernels of ~30 us disappear.
+constexpr int kBatchMax = 96;
+struct NmBatch {
+    void *W[kBatchMax];
+    const float *norms[kBatchMax];
+    uint8_t *mask[kBatchMax];   // all null unless WITH_MASK
+    int64_t rows, cols, ld;
+    int fmode;
+    uint32_t nbx, blocks_per_matrix;
+};
+template <int DT, int M, bool GROUPS_DOWN_ROWS, bool NORM_ALONG, bool WITH_MASK, bool OPTIMISTIC>
+__global__ __launch_bounds__(kBlock) void nm_half_batched_kernel(const NmBatch b)
+{
+    const uint32_t k = blockIdx.x / b.blocks_per_matrix, bid = blockIdx.x - k * b.blocks_per_matrix;
+    if constexpr (GROUPS_DOWN_ROWS)
+        nm_half_rows_body<DT, M, NORM_ALONG, WITH_MASK, OPTIMISTIC>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
+                                                                    WITH_MASK ? b.mask[k] : nullptr, b.nbx, bid);
+    else
+        nm_half_cols_body<DT, M, NORM_ALONG, WITH_MASK, OPTIMISTIC>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
+                                                                    WITH_MASK ? b.mask[k] : nullptr, b.nbx, bid);
+}
 
 // ---------------------------------------------------------------------------
 // Groups run along a row (contiguous in memory): Down-Proj.
@@ -659,6 +705,65 @@ static nm_half_kernel_t pick_half_kernel_mask(bool with_mask, int m, int group_a
                      : pick_half_kernel_m<DT, false>(m, group_axis, norm_axis, varying_factor);
 }
 
+using nm_batched_kernel_t = void (*)(const NmBatch);
+
+template <int DT, int M, bool WITH_MASK>
+static nm_batched_kernel_t pick_batched_kernel(int group_axis, int norm_axis, bool varying_factor)
+{
+    const bool down_rows = group_axis == DASS_AXIS_ROWS, along = norm_axis == group_axis;
+    if (M == 8 && varying_factor)   // see pick_half_kernel
+        return down_rows ? nm_half_batched_kernel<DT, M, true, true, WITH_MASK, M == 8>
+                         : nm_half_batched_kernel<DT, M, false, true, WITH_MASK, M == 8>;
+    if (down_rows)
+        return along ? nm_half_batched_kernel<DT, M, true, true, WITH_MASK, false>
+                     : nm_half_batched_kernel<DT, M, true, false, WITH_MASK, false>;
+    return along ? nm_half_batched_kernel<DT, M, false, true, WITH_MASK, false>
+                 : nm_half_batched_kernel<DT, M, false, false, WITH_MASK, false>;
+}
+
+template <int DT, bool WITH_MASK>
+static nm_batched_kernel_t pick_batched_kernel_m(int m, int group_axis, int norm_axis, bool varying_factor)
+{
+    switch (m) {
+    case 2: return pick_batched_kernel<DT, 2, WITH_MASK>(group_axis, norm_axis, varying_factor);
+    case 4: return pick_batched_kernel<DT, 4, WITH_MASK>(group_axis, norm_axis, varying_factor);
+    case 8: return pick_batched_kernel<DT, 8, WITH_MASK>(group_axis, norm_axis, varying_factor);
+    }
+    return nullptr;
+}
+
+// Launch geometry of the one-pass kernels: one thread per (column slot, row batch), no loop.
+struct HalfGeometry {
+    int block;
+    int64_t nbx, batches;
+};
+static HalfGeometry half_geometry(int64_t rows, int64_t cols, int dt, int group_axis, int m)
+{
+    const int epv = vec_elems(dt);
+    int64_t slots, batches;
+    if (group_axis == DASS_AXIS_COLS) {
+        const int uw = m > epv ? m : epv, rb = kHalfColsRows / (uw / epv);
+        slots = cols / uw;
+        batches = (rows + rb - 1) / rb;
+    } else {
+        slots = cols / epv;
+        const int gb = m >= 4 ? 1 : 2;
+        batches = (rows / m + gb - 1) / gb;
+    }
+    // Workgroup width: the widest of 256, 128, 64 that leaves the fewest idle lanes in the
+    // last workgroup of a row (e.g. 1376 slots: 6 x 256 idles 10 %, 11 x 128 only 2 %).
+    int block = kBlock;
+    for (int cand = kBlock / 2; cand >= 64; cand /= 2)
+        if ((slots + cand - 1) / cand * cand < (slots + block - 1) / block * block)
+            block = cand;
+    return {block, (slots + block - 1) / block, batches};
+}
+
+static bool half_path(double alpha, int n_keep, int m)
+{
+    return 2 * n_keep == m && m <= 8 && (alpha == 0.0 || alpha == 0.5 || alpha == 1.0);
+}
+
 }  // namespace dass
 
 extern "C" size_t dass_nm_workspace_bytes(int64_t rows, int64_t cols, dass_axis norm_axis)
@@ -667,17 +772,14 @@ extern "C" size_t dass_nm_workspace_bytes(int64_t rows, int64_t cols, dass_axis 
     return n > 0 ? dass::round_up((size_t)n * sizeof(float), 256) : 0;
 }
 
-extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, int64_t ld,
-                                          dass_dtype dt, const float *norms, dass_axis norm_axis,
-                                          dass_axis group_axis, double alpha, int n_keep, int m,
-                                          uint8_t *mask_out, void *workspace,
-                                          size_t workspace_bytes, void *hip_stream)
+namespace dass {
+static dass_status check_nm_args(const char *fn, void *W, int64_t rows, int64_t cols, int64_t ld, int dt,
+                                 const float *norms, int norm_axis, int group_axis, double alpha, int n_keep,
+                                 int m, void *workspace, size_t workspace_bytes)
 {
-    using namespace dass;
-    const char *fn = "dass_score_mask_nm";
     dass_status st = check_score_args(fn, W, rows, cols, ld, dt, norms, norm_axis, group_axis, alpha,
                                       workspace, workspace_bytes,
-                                      dass_nm_workspace_bytes(rows, cols, norm_axis));
+                                      dass_nm_workspace_bytes(rows, cols, (dass_axis)norm_axis));
     if (st != DASS_OK)
         return st;
     if (!(m == 2 || m == 4 || m == 8 || m == 16))
@@ -688,34 +790,35 @@ extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, i
     if (len % m != 0)
         return fail(DASS_ERR_SHAPE, "%s: group axis length %lld is not a multiple of m=%d", fn,
                     (long long)len, m);
+    return DASS_OK;
+}
+}  // namespace dass
+
+extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, int64_t ld,
+                                          dass_dtype dt, const float *norms, dass_axis norm_axis,
+                                          dass_axis group_axis, double alpha, int n_keep, int m,
+                                          uint8_t *mask_out, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_score_mask_nm";
+    dass_status st = check_nm_args(fn, W, rows, cols, ld, dt, norms, norm_axis, group_axis, alpha, n_keep, m,
+                                   workspace, workspace_bytes);
+    if (st != DASS_OK)
+        return st;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     // The paper's patterns with an exponent whose factor has an exact f32 recipe: one kernel.
-    if (2 * n_keep == m && m <= 8 && (alpha == 0.0 || alpha == 0.5 || alpha == 1.0)) {
+    if (half_path(alpha, n_keep, m)) {
         const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
-        const int epv = vec_elems(dt);
         const bool varying = norm_axis == group_axis && alpha != 0.0;
         nm_half_kernel_t kernel =
             dt == DASS_BF16 ? pick_half_kernel_mask<DASS_BF16>(mask_out != nullptr, m, group_axis, norm_axis, varying)
                             : pick_half_kernel_mask<DASS_F32>(mask_out != nullptr, m, group_axis, norm_axis, varying);
-        int64_t slots, batches;   // one thread per (column slot, row batch), no loop
-        if (group_axis == DASS_AXIS_COLS) {
-            const int uw = m > epv ? m : epv, rb = kHalfColsRows / (uw / epv);
-            slots = cols / uw;
-            batches = (rows + rb - 1) / rb;
-        } else {
-            slots = cols / epv;
-            const int gb = m >= 4 ? 1 : 2;
-            batches = (rows / m + gb - 1) / gb;
-        }
-        // Workgroup width: the widest of 256, 128, 64 that leaves the fewest idle lanes in the
-        // last workgroup of a row (e.g. 1376 slots: 6 x 256 idles 10 %, 11 x 128 only 2 %).
-        int block = kBlock;
-        for (int cand = kBlock / 2; cand >= 64; cand /= 2)
-            if ((slots + cand - 1) / cand * cand < (slots + block - 1) / block * block)
-                block = cand;
-        const int64_t nbx = (slots + block - 1) / block;
+        const HalfGeometry g = half_geometry(rows, cols, dt, group_axis, m);
+        const int block = g.block;
+        const int64_t nbx = g.nbx, batches = g.batches;
         if (nbx * batches > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: matrix too large for one launch", fn);
         hipLaunchKernelGGL(kernel, dim3((unsigned)(nbx * batches)), dim3(block), 0, stream, W, rows, cols, ld,
@@ -756,4 +859,105 @@ extern "C" dass_status dass_score_mask_nm(void *W, int64_t rows, int64_t cols, i
     hipLaunchKernelGGL(kernel, dim3((unsigned)(nbx * nby)), dim3(kBlock), 0, stream, W, rows, cols,
                        ld, (const float *)f, m - n_keep, mask_out, nbx, nby);
     return check_launch("N:M kernel");
+}
+
+extern "C" size_t dass_nm_batched_workspace_bytes(const dass_nm_task *tasks, int64_t n_tasks)
+{
+    size_t need = 0;
+    for (int64_t i = 0; tasks && i < n_tasks; ++i) {
+        const size_t n = dass_nm_workspace_bytes(tasks[i].rows, tasks[i].cols, tasks[i].norm_axis);
+        need = n > need ? n : need;
+    }
+    return need;
+}
+
+extern "C" dass_status dass_score_mask_nm_batched(const dass_nm_task *tasks, int64_t n_tasks, dass_dtype dt,
+                                                  int n_keep, int m, void *workspace,
+                                                  size_t workspace_bytes, void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_score_mask_nm_batched";
+    if (n_tasks < 0 || (n_tasks > 0 && !tasks))
+        return fail(DASS_ERR_NULL, "%s: tasks must not be NULL", fn);
+    for (int64_t i = 0; i < n_tasks; ++i) {   // validate everything before the first launch
+        const dass_nm_task &t = tasks[i];
+        const dass_status st = check_nm_args(fn, t.W, t.rows, t.cols, t.ld, dt, t.norms, t.norm_axis, t.group_axis,
+                                             t.alpha, n_keep, m, workspace, workspace_bytes);
+        if (st != DASS_OK) {
+            char detail[kErrorBufferSize];
+            snprintf(detail, sizeof detail, "%s", error_buffer());
+            return fail(st, "task %lld: %s", (long long)i, detail);
+        }
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    auto same_launch = [&](const dass_nm_task &a, const dass_nm_task &b) {
+        return a.rows == b.rows && a.cols == b.cols && a.ld == b.ld && a.norm_axis == b.norm_axis &&
+               a.group_axis == b.group_axis && a.alpha == b.alpha && (a.mask_out != nullptr) == (b.mask_out != nullptr);
+    };
+    std::vector<char> done((size_t)n_tasks, 0);
+    for (int64_t i = 0; i < n_tasks; ++i) {
+        if (done[(size_t)i])
+            continue;
+        const dass_nm_task &t = tasks[i];
+        if (!half_path(t.alpha, n_keep, m)) {
+            const dass_status st = dass_score_mask_nm(t.W, t.rows, t.cols, t.ld, dt, t.norms, t.norm_axis, t.group_axis,
+                                                      t.alpha, n_keep, m, t.mask_out, workspace, workspace_bytes,
+                                                      hip_stream);
+            if (st != DASS_OK)
+                return st;
+            done[(size_t)i] = 1;
+            continue;
+        }
+        const HalfGeometry g = half_geometry(t.rows, t.cols, dt, t.group_axis, m);
+        const int64_t per_matrix = g.nbx * g.batches;
+        if (per_matrix > 0x7fffffffLL)
+            return fail(DASS_ERR_SHAPE, "%s: task %lld: matrix too large for one launch", fn, (long long)i);
+        const bool varying = t.norm_axis == t.group_axis && t.alpha != 0.0;
+        const bool with_mask = t.mask_out != nullptr;
+        nm_batched_kernel_t kernel =
+            dt == DASS_BF16 ? (with_mask ? pick_batched_kernel_m<DASS_BF16, true>(m, t.group_axis, t.norm_axis, varying)
+                                         : pick_batched_kernel_m<DASS_BF16, false>(m, t.group_axis, t.norm_axis, varying))
+                            : (with_mask ? pick_batched_kernel_m<DASS_F32, true>(m, t.group_axis, t.norm_axis, varying)
+                                         : pick_batched_kernel_m<DASS_F32, false>(m, t.group_axis, t.norm_axis, varying));
+        NmBatch b;
+        b.rows = t.rows;
+        b.cols = t.cols;
+        b.ld = t.ld;
+        b.fmode = t.alpha == 0.0 ? kFactorOne : t.alpha == 1.0 ? kFactorNorm : kFactorSqrt;
+        b.nbx = (uint32_t)g.nbx;
+        b.blocks_per_matrix = (uint32_t)per_matrix;
+        const int64_t fit = 0x7fffffffLL / per_matrix;   // matrices one grid can hold
+        const int cap = (int)(fit < kBatchMax ? fit : kBatchMax);
+        int n = 0;
+        auto flush = [&]() -> dass_status {
+            if (n == 0)
+                return DASS_OK;
+            for (int k = n; k < kBatchMax; ++k) {
+                b.W[k] = nullptr;
+                b.norms[k] = nullptr;
+                b.mask[k] = nullptr;
+            }
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(per_matrix * n)), dim3(g.block), 0, stream, b);
+            n = 0;
+            return check_launch("batched N:M kernel");
+        };
+        for (int64_t j = i; j < n_tasks; ++j) {   // every later task that can share this launch
+            if (done[(size_t)j] || !same_launch(t, tasks[j]))
+                continue;
+            b.W[n] = tasks[j].W;
+            b.norms[n] = tasks[j].norms;
+            b.mask[n] = tasks[j].mask_out;
+            done[(size_t)j] = 1;
+            if (++n == cap) {
+                const dass_status st = flush();
+                if (st != DASS_OK)
+                    return st;
+            }
+        }
+        const dass_status st = flush();
+        if (st != DASS_OK)
+            return st;
+    }
+    return DASS_OK;
 }

@@ -97,3 +97,30 @@ def test_calib_rejections(lib):
     assert call(ldx=32) == "DASS_ERR_SHAPE"
     assert call(X=ODD) == "DASS_ERR_ALIGN"
     assert call(ldw=68) == "DASS_ERR_ALIGN"
+
+
+def _task(W=FAKE, rows=64, cols=64, ld=64, norms=FAKE, na=1, ga=1, alpha=1.0, mask=None):
+    return binding.NmTask(W.value if W else None, rows, cols, ld, norms.value if norms else None, na, ga, alpha, mask)
+
+
+def _batched(lib, tasks, dt=1, n=2, m=4, ws=FAKE, wsb=4096):
+    arr = (binding.NmTask * max(len(tasks), 1))(*tasks)
+    st = lib.dass_score_mask_nm_batched(arr, len(tasks), dt, n, m, ws, wsb, None)
+    return lib.dass_status_string(st).decode(), lib.dass_last_error_string().decode()
+
+
+def test_batched_rejections_name_the_task(lib):
+    """Every task is checked before anything is launched; the message carries the offender's index."""
+    good = _task()
+    assert _batched(lib, [])[0] == "DASS_OK"                       # nothing to do
+    name, text = _batched(lib, [good, _task(W=None)])
+    assert name == "DASS_ERR_NULL" and "task 1" in text
+    name, text = _batched(lib, [good, good, _task(cols=60)])
+    assert name == "DASS_ERR_SHAPE" and "task 2" in text
+    assert _batched(lib, [good], m=3)[0] == "DASS_ERR_ARG"
+    assert _batched(lib, [good], n=4, m=4)[0] == "DASS_ERR_ARG"
+    assert _batched(lib, [_task(W=ODD)])[0] == "DASS_ERR_ALIGN"
+    assert _batched(lib, [good], wsb=16)[0] == "DASS_ERR_WORKSPACE"
+    assert lib.dass_score_mask_nm_batched(None, 3, 1, 2, 4, FAKE, 4096, None) != 0
+    arr = (binding.NmTask * 2)(_task(rows=4096, cols=11008, ld=11008), _task(rows=11008, cols=4096, ld=4096, na=0, ga=0))
+    assert lib.dass_nm_batched_workspace_bytes(arr, 2) >= 4 * 11008
