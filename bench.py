@@ -235,14 +235,25 @@ def main():
             for w, n, na, ga, al in tasks:
                 dass.score_mask_nm(w, n, na, ga, al, n_keep, m, workspace=ws_model)
 
+        ws_u = torch.empty(max(16, dass.unstructured_workspace_bytes(I, d, Wg.dtype, "rows", "rows"),
+                               dass.unstructured_workspace_bytes(d, I, Wd.dtype, "cols", "cols")),
+                           dtype=torch.uint8, device=dev)
+
+        def unstructured_half():   # 50 % per comparison group, the paper's default setting
+            for w, n, na, ga, al in tasks:
+                dass.score_mask_unstructured(w, n, na, ga, al, I // 2, workspace=ws_u)
+
         ms_batched = timed(lambda: dass.score_mask_nm_batched(tasks, n_keep, m, workspace=ws_model))
         ms_single = timed(one_by_one)
+        ms_unstructured = timed(unstructured_half)
         model_bytes = 3 * L * bytes_per_matrix
         model = {"layers": L, "matrices": 3 * L, "bytes": model_bytes,
                  "batched_ms": ms_batched, "batched_GBps": model_bytes / (ms_batched * 1e-3) / 1e9,
                  "batched_frac_of_hbm_peak": model_bytes / (ms_batched * 1e-3) / 1e9 / PEAK_HBM_GBS,
                  "one_call_per_matrix_ms": ms_single,
-                 "one_call_per_matrix_GBps": model_bytes / (ms_single * 1e-3) / 1e9}
+                 "one_call_per_matrix_GBps": model_bytes / (ms_single * 1e-3) / 1e9,
+                 "unstructured_50pct_ms": ms_unstructured,
+                 "unstructured_50pct_GBps": model_bytes / (ms_unstructured * 1e-3) / 1e9}
         del layers, tasks
 
     out = {

@@ -485,33 +485,30 @@ __device__ __forceinline__ bool lr_settle(const uint32_t *hist, LrState *state, 
     int lane = threadIdx.x & 63;
     asm volatile("" : "+v"(lane));   // keeps the per-lane bin numbers out of the caller's loop-invariant registers
     const LrState st = *state;
-    uint32_t h[32], sum = 0;
+    const uint32_t *mine = hist + kLrBins - 32 * (lane + 1);   // the lane's 32 bins, ascending
+    uint32_t sum = 0;
     bool alarm = false;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {   // ascending addresses: h[31 - 4q - 3 .. 31 - 4q]
-        const u32x4 x = *reinterpret_cast<const u32x4 *>(hist + kLrBins - 32 * (lane + 1) + 4 * q);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            h[31 - 4 * q - i] = x[i];
-            sum += x[i];
-            alarm |= x[i] != 0 && (uint32_t)(kLrBins - 32 * (lane + 1)) + (uint32_t)(4 * q + i) >= alarm_bin;
-        }
+#pragma clang loop unroll(disable)
+    for (int q = 0; q < 8; ++q) {
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(mine + 4 * q);
+        sum += x[0] + x[1] + x[2] + x[3];
+        alarm |= (x[0] | x[1] | x[2] | x[3]) != 0 && (uint32_t)(kLrBins - 32 * (lane + 1) + 4 * q + 3) >= alarm_bin;
     }
     const uint32_t incl = wave_inclusive_scan(sum);
     uint32_t excl = incl - sum;
     uint32_t my_digit = 0xFFFFFFFFu, my_above = 0, my_inside = 0;
-    if (excl < st.need && st.need <= incl) {
-        uint32_t my_j = 32;
-#pragma unroll
-        for (int j = 0; j < 32; ++j) {   // h[j] counts bin 2047 - 32 lane - j
-            if (my_j == 32 && st.need <= excl + h[j]) {
-                my_j = j;
+    if (excl < st.need && st.need <= incl) {   // one lane: walk its bins from the highest down
+#pragma clang loop unroll(disable)
+        for (int j = 31; j >= 0; --j) {
+            const uint32_t h = mine[j];
+            if (st.need <= excl + h) {
+                my_digit = kLrBins - 32 * (lane + 1) + j;
                 my_above = excl;
-                my_inside = h[j];
+                my_inside = h;
+                break;
             }
-            excl += h[j];
+            excl += h;
         }
-        my_digit = kLrBins - 1 - 32 * lane - my_j;
     }
     const uint64_t found = __ballot(my_digit != 0xFFFFFFFFu);   // exactly one lane: 1 <= need <= candidates
     const int src = found ? __ffsll((long long)found) - 1 : 0;
@@ -791,14 +788,31 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             b = (uint32_t)k;
         }
     };
-    // The rare passes (fields B and C, f64 form) go through one copy of the code: the loop
-    // handles the vector in v[0] and rotates the array, so that after VPT turns it is back in place.
-    auto rotate = [&]() __attribute__((always_inline)) {
-        const u32x4 first = v[0];
+    // The rare passes (fields B and C, f64 form) work from memory, where the weights are still
+    // unmodified, in loops that are not laid out per vector: they cost the common passes neither
+    // registers nor code.
+    // Element e of a vector and its scaled factor, e known only at run time: the rare passes loop
+    // over the elements too, so that they need few registers beside the 16 data vectors.
+    auto word_at = [](const u32x4 &x, int k) { return k == 0 ? x[0] : k == 1 ? x[1] : k == 2 ? x[2] : x[3]; };
+    auto elem_at = [&](const u32x4 &x, int e) {
+        if constexpr (DT == DASS_BF16) {
+            const uint32_t w = word_at(x, e >> 1);
+            return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+        } else {
+            return __uint_as_float(word_at(x, e));
+        }
+    };
+    auto zero_at_if = [](u32x4 &x, int e, bool drop) {
+        const int k = DT == DASS_BF16 ? e >> 1 : e;
+        const uint32_t m = !drop ? 0xffffffffu : DT == DASS_BF16 ? ((e & 1) ? 0x0000ffffu : 0xffff0000u) : 0u;
 #pragma unroll
-        for (int i = 0; i + 1 < VPT; ++i)
-            v[i] = v[i + 1];
-        v[VPT - 1] = first;
+        for (int i = 0; i < 4; ++i)
+            x[i] &= i == k ? m : 0xffffffffu;
+    };
+    auto factor_at = [&](int j, uint32_t t, int e, int line) {
+        if (FACTOR_ALONG)
+            return fl[GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e];
+        return fl[line];
     };
     auto count_any = [&](const LrPass ps, uint32_t wmask, uint32_t himask) __attribute__((always_inline)) {
         const uint32_t t = fresh_tid();
@@ -806,37 +820,39 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
         for (int j = 0; j < VPT; ++j) {
             const int line0 = vec_line0(j);
             if (vec_valid(j, t)) {
-                float fs[EPV];
-                vec_factors(j, t, line0, fs);
-#pragma unroll
+                const u32x4 x = *reinterpret_cast<const u32x4 *>(vec_addr(j, t));   // still unmodified in memory
+#pragma clang loop unroll(disable)
                 for (int e = 0; e < EPV; ++e) {
                     const int line = GATE ? line0 + e : line0;
-                    const LrState st = state[line];
-                    const int64_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+                    if (!state[line].open)
+                        continue;
+                    const uint32_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
                     uint32_t a, b;
-                    fields(elem_of<DT>(v[0], e), fs[e], norm_index(j, t, e, line), true, a, b);
-                    const uint32_t c = 0xFFFFu - (uint32_t)idx;
-                    bool cand = st.open != 0;
+                    fields(elem_at(x, e), factor_at(j, t, e, line), norm_index(j, t, e, line), true, a, b);
+                    const uint32_t c = 0xFFFFu - idx;
+                    const uint32_t ta = state[line].a, tb = state[line].b, tc = state[line].c;
+                    bool cand;
                     uint32_t x;
                     if (ps.field == 0) {
-                        cand = cand && ((a ^ st.a) & himask) == 0;
+                        cand = ((a ^ ta) & himask) == 0;
                         x = a;
                     } else if (ps.field == 1) {
-                        cand = cand && a == st.a && ((b ^ st.b) & himask) == 0;
+                        cand = (a == ta) & (((b ^ tb) & himask) == 0);
                         x = b;
                     } else {
-                        cand = cand && a == st.a && b == st.b && ((c ^ st.c) & himask) == 0;
+                        cand = (a == ta) & (b == tb) & (((c ^ tc) & himask) == 0);
                         x = c;
                     }
                     if (cand)
                         atomicAdd(hist + line * kLrBins + ((x >> ps.shift) & wmask), 1u);
                 }
             }
-            rotate();
         }
     };
 
-    for (int pass = 0;; ++pass) {
+    // One counting pass and its settling.  Wavefront l settles line l; a product that became
+    // infinite shows in the first digit of p.  Leaves flags[0] = a line is still open.
+    auto run_pass = [&](int pass, auto fast_tag) __attribute__((always_inline)) {
         for (int i = tid; i < kLrLines * kLrBins / 4; i += NT)
             reinterpret_cast<u32x4 *>(hist)[i] = u32x4{0, 0, 0, 0};
         if (tid == 0)
@@ -845,15 +861,15 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
         const LrPass ps = lr_pass(pass);
         const uint32_t wmask = (1u << ps.width) - 1u;
         const uint32_t himask = ps.shift + ps.width >= 32 ? 0u : ~0u << (ps.shift + ps.width);
-        if (ps.field == 0 && !exact)
+        if constexpr (decltype(fast_tag)::value)
             count_fast(ps.shift, wmask, himask);
         else
             count_any(ps, wmask, himask);
         __syncthreads();
-        // wavefront l settles line l; a product that became infinite shows in the first digit of p
         const int wave = tid / 64;
         if (wave < n_lines && state[wave].open) {   // uniform inside the wavefront
-            const uint32_t alarm_bin = (!exact && pass == 0) ? (0x7f800000u >> 21) : (uint32_t)kLrBins;
+            const uint32_t alarm_bin =
+                (decltype(fast_tag)::value && pass == 0) ? (0x7f800000u >> 21) : (uint32_t)kLrBins;
             const bool alarm = lr_settle(hist + wave * kLrBins, state + wave, ps, pass, alarm_bin);
             if ((tid & 63) == 0) {
                 if (state[wave].open)
@@ -863,19 +879,28 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             }
         }
         __syncthreads();
-        if (!exact && flags[1]) {   // start again on f64 products (uniform)
-            exact = true;
-            reset_state();
-            pass = -1;
-            __syncthreads();
-            continue;
+    };
+
+    // The three passes on field A in the two-term form, then the ties.
+    bool open_lines = true;
+    if (!exact) {
+        for (int pass = 0; pass < 3; ++pass) {
+            run_pass(pass, std::true_type{});
+            if (flags[1]) {   // start again on f64 products (uniform)
+                exact = true;
+                reset_state();
+                break;
+            }
+            open_lines = flags[0] != 0;
+            if (!open_lines)
+                break;   // uniform
+            __syncthreads();   // flags[0] is cleared at the top of the next pass
         }
-        if (!flags[0])
-            break;   // uniform
-        __syncthreads();   // flags[0] is cleared at the top of the next pass
-        if (pass == 2 && !exact) {   // field A is decided and some line has ties on it
+        __syncthreads();
+        if (!exact && open_lines) {   // field A is decided and some line has ties on it
             collect_ties();
             __syncthreads();
+            const int wave = tid / 64;
             if (wave < n_lines && state[wave].open)   // uniform inside the wavefront
                 rank_ties(wave);
             if (tid == 0)
@@ -884,6 +909,15 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             if (tid < n_lines && state[tid].open)
                 flags[0] = 1;
             __syncthreads();
+            open_lines = flags[0] != 0;
+            __syncthreads();
+        }
+    }
+    // What is left (a tie list that overflowed: from field B on; the f64 form: from the start)
+    // goes digit by digit through the code that works from memory.
+    if (exact || open_lines) {
+        for (int pass = exact ? 0 : 3;; ++pass) {
+            run_pass(pass, std::false_type{});
             if (!flags[0])
                 break;   // uniform
             __syncthreads();
@@ -983,25 +1017,23 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             const bool valid = vec_valid(j, t);
             uint32_t kept = 0;
             if (valid) {
-                float fs[EPV];
-                vec_factors(j, t, line0, fs);
-#pragma unroll
+                u32x4 x = *reinterpret_cast<const u32x4 *>(vec_addr(j, t));
+#pragma clang loop unroll(disable)
                 for (int e = 0; e < EPV; ++e) {
                     const int line = GATE ? line0 + e : line0;
-                    const int64_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
+                    const uint32_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
                     uint32_t a, b;
-                    fields(elem_of<DT>(v[0], e), fs[e], norm_index(j, t, e, line), true, a, b);
-                    const bool keep = lr_keep(state[line], a, b, 0xFFFFu - (uint32_t)idx);
-                    zero_lane_if<DT>(v[0], e, !keep);
+                    fields(elem_at(x, e), factor_at(j, t, e, line), norm_index(j, t, e, line), true, a, b);
+                    const bool keep = lr_keep(state[line], a, b, 0xFFFFu - idx);
+                    zero_at_if(x, e, !keep);
                     kept |= (keep ? 1u : 0u) << e;
                 }
-                __builtin_nontemporal_store(v[0], reinterpret_cast<u32x4 *>(vec_addr(j, t)));
+                *reinterpret_cast<u32x4 *>(vec_addr(j, t)) = x;
             }
             if (!GATE && EPV == 4)
                 row_bits = __shfl_xor(kept, 1, 64);
             if (valid)
                 write_mask(j, t, line0, kept, row_bits);
-            rotate();
         }
     }
 }

@@ -60,6 +60,9 @@ CONFIGS = {
                   nm=((4, 8),)),
         MlpConfig("llama2_70b", 8192, 28672, 262144, "bf16", "silu", 32768, 1e-3,
                   nm=((2, 4),)),
+        # a sixth shape beside the five benchmark ones: LLaMA2-13B (the appendix table of model configurations)
+        MlpConfig("llama2_13b", 5120, 13824, 262144, "bf16", "silu", 262144, 1e-3,
+                  nm=((2, 4), (4, 8))),
     ]
 }
 
