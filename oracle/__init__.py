@@ -44,6 +44,8 @@ def _load():
         lib.oracle_act.argtypes = [dbl, ci]
         lib.oracle_sumsq.restype = None
         lib.oracle_sumsq.argtypes = [vp, i64, i64, vp, vp, i64, i64, i64, ci, vp, i64, vp]
+        lib.oracle_input_sumsq.restype = None
+        lib.oracle_input_sumsq.argtypes = [vp, i64, i64, i64, vp]
         lib.oracle_norms.restype = None
         lib.oracle_norms.argtypes = [vp, i64, vp]
         lib.oracle_factor.restype = None
@@ -116,6 +118,18 @@ def sumsq(X, Wg, Wu, kind: str, neurons=None, out=None) -> np.ndarray:
     _load().oracle_sumsq(_ptr(X), T, _ld(X), _ptr(Wg), _ptr(Wu), _ld(Wg),
                          d, d_int, ACT[kind],
                          None if neurons is None else _ptr(neurons), n, _ptr(out))
+    return out
+
+
+def input_sumsq(X, out=None) -> np.ndarray:
+    """Add sum_t X[t, j]^2 (Eq. 1: the squared input-feature norms) into ``out`` (float64)."""
+    X = _f32_2d(X, "X")
+    T, d = X.shape
+    if out is None:
+        out = np.zeros(d, dtype=np.float64)
+    if out.dtype != np.float64 or out.shape != (d,) or not out.flags.c_contiguous:
+        raise TypeError("out: need contiguous float64 of length d")
+    _load().oracle_input_sumsq(_ptr(X), T, _ld(X), d, _ptr(out))
     return out
 
 

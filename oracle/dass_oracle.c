@@ -18,6 +18,7 @@
  *   - oracle_mask_nm              : Sec. 3 "Extension to N:M Sparsity" on the
  *     scores of Eq. 4 / Eq. 5.
  *   - oracle_mask_unstructured    : Sec. 3 "Pruning Granularity".
+ *   - oracle_input_sumsq          : Sec. 2.1 Eq. 1, the input-feature norms of the Wanda metric.
  *
  * Inputs are float arrays holding exactly the values the GPU sees (a bf16
  * value widens to float without rounding); all arithmetic is double.  The
@@ -31,7 +32,8 @@
  * Pins: tests/test_oracle_*.py (brute force over all subsets, group-count
  * invariants, alpha = 0 magnitude pruning, the Wanda reduction of Eq. 5,
  * scale invariance, Gram-matrix closed forms for the norms, activation spot
- * values, chunk additivity).  No function here is "parity unpinned".
+ * values, chunk additivity; sums of squares of integers and a hand-worked Wanda selection for
+ * the input norms).  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -96,6 +98,25 @@ void oracle_sumsq(const float *X, int64_t T, int64_t ldx,
             acc += y * y;
         }
         sumsq[k] += acc;
+    }
+}
+
+/*
+ * Eq. 1 (the Wanda metric, which the Down-Proj score of Eq. 5 has the form of): the L2 norm of
+ * every input feature over all tokens, ||X_j||_2.  Here its square:
+ *   X : [T, d] row-major, row stride ldx;  sumsq : d doubles, ADDED to (token chunks accumulate)
+ *   sumsq[j] += sum over t of X[t, j]^2, tokens in natural order, in double.
+ */
+void oracle_input_sumsq(const float *X, int64_t T, int64_t ldx, int64_t d, double *sumsq)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d; ++j) {
+        double acc = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            const double x = (double)X[t * ldx + j];
+            acc += x * x;
+        }
+        sumsq[j] += acc;
     }
 }
 
