@@ -204,6 +204,24 @@ def main():
     s2_gbs = 3 * bytes_per_matrix / (s2_avg * 1e-3) / 1e9
     cold_call_us = (2 * cold["gate"]["median_us"] + cold["down"]["median_us"]) / 3.0
 
+    # ---- the Wanda metric's input-feature norms over the same tokens (reads X once) ------------
+    in_sumsq = torch.empty(d, device=dev)
+    in_norms = torch.empty(d, device=dev)
+    ws_in = torch.empty(max(16, dass.input_norms_workspace_bytes(T, d)), dtype=torch.uint8, device=dev)
+    in_ms = []
+    for it in range(5):
+        a, b = ev(), ev()
+        a.record()
+        dass.input_norms(X, in_sumsq, norms_out=in_norms, workspace=ws_in)
+        b.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            in_ms.append(a.elapsed_time(b))
+    in_ms = statistics.median(in_ms)
+    in_bytes = float(T) * d * esz
+    input_norms = {"ms": in_ms, "GBps": in_bytes / (in_ms * 1e-3) / 1e9,
+                   "frac_of_hbm_peak": in_bytes / (in_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": in_bytes}
+
     # ---- stage 2 for a whole model: all layers x (gate, up, down), batched against one call each ----
     model = None
     if args.model_layers > 0:
@@ -279,6 +297,7 @@ def main():
                    "cold_single_launch_GBps": bytes_per_matrix / (cold_call_us * 1e-6) / 1e9,
                    "bytes_per_matrix": bytes_per_matrix},
     }
+    out["input_norms_eq1"] = input_norms
     if model is not None:
         out["stage2_whole_model"] = model
     if not args.no_cpu_baseline:

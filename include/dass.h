@@ -161,6 +161,31 @@ dass_status dass_score_mask_nm_batched(const dass_nm_task *tasks, int64_t n_task
                                        size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The input-feature norms of the Wanda metric (Sec. 2.1 Eq. 1): for every
+ * input feature j the L2 norm of X[:, j] over all tokens,
+ *
+ *   sumsq[j] (+)= sum_t X[t, j]^2,      norms_out[j] = sqrt(sumsq[j]).
+ *
+ * With these norms, dass_score_mask_nm(W, ..., norm_axis = group_axis = COLS,
+ * alpha = 1) on a [d_out, d_in] matrix is the paper's comparison system
+ * (output-balanced |W| * ||X_j||, Eq. 1), and Eq. 5 is the same call on
+ * Down-Proj with the stage-1 norms.
+ *
+ *   X      [T, d] row stride ldx, dtype dt, read only; d a multiple of 8
+ *   sumsq  f32[d]; overwritten, or added to when accumulate != 0 (token chunks)
+ *   norms_out  NULL or f32[d]
+ *   workspace  device scratch of at least dass_input_norms_workspace_bytes()
+ *          bytes, 16-byte aligned (per-row-block partial sums; the result does
+ *          not depend on scheduling)
+ * Squares and block sums are f32, the sum over blocks f64.
+ */
+size_t dass_input_norms_workspace_bytes(int64_t T, int64_t d);
+
+dass_status dass_input_norms(const void *X, int64_t T, int64_t ldx, int64_t d, dass_dtype dt,
+                             float *sumsq, int accumulate, float *norms_out, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/*
  * Stage 2 -- DaSS scoring with per-line unstructured selection (Sec. 3
  * "Pruning Granularity": weights are compared for each input individually for
  * Gate/Up, for each output individually for Down, and the lowest scores of

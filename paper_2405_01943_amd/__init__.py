@@ -7,6 +7,7 @@ device memory and streams.
 from .binding import (  # noqa: F401
     ACT, AXIS, DTYPE, DassError,
     calib_norms, calib_workspace_bytes,
+    input_norms, input_norms_workspace_bytes,
     score_mask_nm, nm_workspace_bytes,
     score_mask_nm_batched, nm_batched_workspace_bytes,
     score_mask_unstructured, unstructured_workspace_bytes,

@@ -25,6 +25,7 @@ EXPORTS = (
     "dass_nm_workspace_bytes", "dass_score_mask_nm",
     "dass_nm_batched_workspace_bytes", "dass_score_mask_nm_batched",
     "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
+    "dass_input_norms_workspace_bytes", "dass_input_norms",
     "dass_status_string", "dass_last_error_string", "dass_version",
 )
 
@@ -82,6 +83,10 @@ def load_library() -> ctypes.CDLL:
     lib.dass_score_mask_unstructured.restype = ci
     lib.dass_score_mask_unstructured.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, i64, vp,
                                                  vp, sz, vp]
+    lib.dass_input_norms_workspace_bytes.restype = sz
+    lib.dass_input_norms_workspace_bytes.argtypes = [i64, i64]
+    lib.dass_input_norms.restype = ci
+    lib.dass_input_norms.argtypes = [vp, i64, i64, i64, ci, vp, ci, vp, vp, sz, vp]
     lib.dass_status_string.restype = ctypes.c_char_p
     lib.dass_status_string.argtypes = [ci]
     lib.dass_last_error_string.restype = ctypes.c_char_p
@@ -150,6 +155,26 @@ def calib_norms(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, act: st
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.dass_calib_norms(_ptr(X), T, ldx, _ptr(Wgate), _ptr(Wup), ldw, d, d_int,
                                 DTYPE[X.dtype], ACT[act], _ptr(sumsq), int(bool(accumulate)),
+                                _ptr(norms_out), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def input_norms_workspace_bytes(T: int, d: int) -> int:
+    return int(load_library().dass_input_norms_workspace_bytes(T, d))
+
+
+def input_norms(X: torch.Tensor, sumsq: torch.Tensor, accumulate: bool = False,
+                norms_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                stream=None) -> None:
+    """dass_input_norms: sumsq[j] (+)= sum_t X[t, j]^2 (the Wanda metric's input norms, Eq. 1)."""
+    lib = load_library()
+    T, d, ldx = _matrix(X, "X")
+    for name, t in (("sumsq", sumsq), ("norms_out", norms_out)):
+        if t is not None and (t.dtype != torch.float32 or t.numel() != d or not t.is_contiguous()):
+            raise TypeError(f"{name}: need contiguous float32[d]")
+    if workspace is None:
+        workspace = _scratch(int(lib.dass_input_norms_workspace_bytes(T, d)), X.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.dass_input_norms(_ptr(X), T, ldx, d, DTYPE[X.dtype], _ptr(sumsq), int(bool(accumulate)),
                                 _ptr(norms_out), _ptr(workspace), ws_bytes, _stream(stream)))
 
 

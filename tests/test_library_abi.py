@@ -124,3 +124,23 @@ def test_batched_rejections_name_the_task(lib):
     assert lib.dass_score_mask_nm_batched(None, 3, 1, 2, 4, FAKE, 4096, None) != 0
     arr = (binding.NmTask * 2)(_task(rows=4096, cols=11008, ld=11008), _task(rows=11008, cols=4096, ld=4096, na=0, ga=0))
     assert lib.dass_nm_batched_workspace_bytes(arr, 2) >= 4 * 11008
+
+
+def _inorm(lib, X=FAKE, T=64, ldx=64, d=64, dt=1, sumsq=FAKE, norms=None, ws=FAKE, wsb=1 << 20):
+    return lib.dass_status_string(lib.dass_input_norms(X, T, ldx, d, dt, sumsq, 0, norms, ws, wsb, None)).decode()
+
+
+def test_input_norms_rejections(lib):
+    assert _inorm(lib, X=None) == "DASS_ERR_NULL"
+    assert _inorm(lib, sumsq=None) == "DASS_ERR_NULL"
+    assert _inorm(lib, dt=7) == "DASS_ERR_DTYPE"
+    assert _inorm(lib, T=0) == "DASS_ERR_SHAPE"
+    assert _inorm(lib, d=60) == "DASS_ERR_SHAPE"
+    assert _inorm(lib, ldx=56) == "DASS_ERR_SHAPE"
+    assert _inorm(lib, X=ODD) == "DASS_ERR_ALIGN"
+    assert _inorm(lib, norms=ODD) == "DASS_ERR_ALIGN"
+    assert _inorm(lib, ldx=68, dt=1) == "DASS_ERR_ALIGN"        # bf16 rows must start on 16 bytes
+    assert _inorm(lib, ws=None) == "DASS_ERR_WORKSPACE"
+    assert _inorm(lib, wsb=64) == "DASS_ERR_WORKSPACE"
+    assert lib.dass_input_norms_workspace_bytes(262144, 4096) >= 1024 * 4096 * 4
+    assert lib.dass_input_norms_workspace_bytes(0, 4096) == 0
