@@ -14,7 +14,7 @@
 namespace dass {
 
 constexpr int kInBlock = 256;     // threads = column slots per workgroup
-constexpr int kInRows = 256;      // rows per row block
+constexpr int kInRows = 512;      // rows per row block
 constexpr int kInUnroll = 8;      // rows in flight per thread
 
 template <int DT>

@@ -12,9 +12,9 @@ from gpu_helpers import bits_equal, first_mismatch, padded, to_np32
 
 pytestmark = pytest.mark.gpu
 
-# f32 squares and 256-row block sums, f64 across blocks: the relative error of a sum of
-# non-negative terms stays below 256 * 2^-24 = 1.6e-5; observed ~1e-7.
-TOL = 2e-5
+# f32 squares and 512-row block sums, f64 across blocks: the relative error of a sum of
+# non-negative terms stays below 512 * 2^-24 = 3.1e-5; observed ~5e-7.
+TOL = 4e-5
 
 
 def _rel_err(got, want):
