@@ -115,3 +115,21 @@ def test_batched_error_leaves_every_matrix_untouched(gpu_device):
     assert "task 2" in str(e.value)
     torch.cuda.synchronize()
     assert all(torch.all(w == 1) for w in W)
+
+
+def test_batched_full_size_layers(gpu_device):
+    """Three layers of the LLaMA2-7B-shaped config through one batched call, as bench.py launches
+    it (Gate/Up share one launch, Down another); every weight of all nine matrices is compared."""
+    from paper_2405_01943_amd import synth
+    cfg = synth.CONFIGS["llama2_7b"]
+    dev = gpu_device
+    base = [synth.make_weight(cfg, w, dev, seed=s) for s in range(3) for w in ("wg", "wu", "wd")]
+    norms = [synth.make_norms(cfg.d_int, dev, seed=s) for s in range(3)]
+    work = [w.clone() for w in base]
+    kinds = (("rows", "rows", cfg.alpha_gate_up), ("rows", "rows", cfg.alpha_gate_up), ("cols", "cols", cfg.alpha_down))
+    tasks = [(work[3 * s + k], norms[s], kinds[k][0], kinds[k][1], kinds[k][2]) for s in range(3) for k in range(3)]
+    dass.score_mask_nm_batched(tasks, 2, 4)
+    torch.cuda.synchronize()
+    for s in range(3):
+        for k in range(3):
+            _check(work[3 * s + k], base[3 * s + k], norms[s], kinds[k][:2], kinds[k][2], 2, 4)
