@@ -416,9 +416,11 @@ __global__ __launch_bounds__(kUBlock) void unstructured_rows_kernel(
 
 
 // ===========================================================================
-// Line-resident kernels: lines of up to 16384 (bf16) / 8192 (f32) weights with alpha in
-// {0, 0.5, 1}.  A 1024-thread workgroup holds 8 lines in its registers, so the weights are read
-// once and written once; all selection passes run on the registers.
+// Line-resident kernels, alpha in {0, 0.5, 1}: a 1024-thread workgroup holds up to 8 lines in its
+// registers (131072 bf16 / 65536 f32 weights in all), so the weights are read once and written
+// once; all selection passes run on the registers.  Column lines: up to 16384 (bf16) / 8192 (f32)
+// rows; row lines: any length below 65536 whose factors fit LDS beside the histograms (8, 4, 2 or
+// 1 lines per workgroup).
 //
 // Order of positions in a line: (score descending, index ascending), encoded as a composite
 // of three 32-bit fields (A, B, C) compared lexicographically, larger = kept first:
@@ -556,8 +558,8 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     constexpr int VR = 8 / EPV;
     constexpr bool GATE = LAYOUT == kLrGate;
     extern __shared__ __attribute__((aligned(16))) char lr_smem[];
-    uint32_t *hist = reinterpret_cast<uint32_t *>(lr_smem);                           // [kLrLines][kLrBins]
-    LrState *state = reinterpret_cast<LrState *>(lr_smem + kLrLines * kLrBins * 4);   // [kLrLines]
+    uint32_t *hist = reinterpret_cast<uint32_t *>(lr_smem);                           // [lines_per_block][kLrBins]
+    LrState *state = reinterpret_cast<LrState *>(lr_smem + (size_t)lines_per_block * kLrBins * 4);   // [kLrLines]
     uint32_t *flags = reinterpret_cast<uint32_t *>(state + kLrLines);                 // [0] a line is open, [1] f64 form wanted
     uint32_t *trash = flags + 4;                                                      // [64] counters nobody reads
     uint32_t *tie_count = trash + 64;                                                 // [kLrLines]
@@ -853,7 +855,7 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     // One counting pass and its settling.  Wavefront l settles line l; a product that became
     // infinite shows in the first digit of p.  Leaves flags[0] = a line is still open.
     auto run_pass = [&](int pass, auto fast_tag) __attribute__((always_inline)) {
-        for (int i = tid; i < kLrLines * kLrBins / 4; i += NT)
+        for (int i = tid; i < lines_per_block * kLrBins / 4; i += NT)
             reinterpret_cast<u32x4 *>(hist)[i] = u32x4{0, 0, 0, 0};
         if (tid == 0)
             flags[0] = 0;
@@ -1101,7 +1103,7 @@ extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64
                 lpb = kLrVecs >> vpl_log2;
             grid = (rows + lpb - 1) / lpb;
         }
-        const size_t smem = (size_t)kLrLines * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 + 256 +
+        const size_t smem = (size_t)lpb * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 + 256 +
                             kLrLines * 4 + kLrLines * kLrTies * 8 +
                             (along ? (size_t)len : (size_t)kLrLines) * sizeof(float);
         if (fits && grid <= 0x7fffffffLL && smem <= 160 * 1024 && rows * ld * (bf16 ? 2 : 4) < (1LL << 32)) {

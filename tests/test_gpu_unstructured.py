@@ -160,6 +160,26 @@ def test_unstructured_mistral_shaped_lines(gpu_device):
     assert bits_equal(Wg, want_g), first_mismatch(Wg, want_g)
 
 
+@pytest.mark.parametrize("dtype,cols", [(torch.bfloat16, 28672), (torch.bfloat16, 24576), (torch.float32, 14336),
+                                        (torch.bfloat16, 20000), (torch.bfloat16, 40000)])
+def test_unstructured_long_row_lines(gpu_device, dtype, cols):
+    """Row lines longer than a workgroup holds 8 of: 4, 2 or 1 lines per workgroup, a ragged last
+    workgroup (LLaMA2-70B and Gemma-7B Down-Proj rows among them)."""
+    rows = 7
+    g = torch.Generator(device="cpu").manual_seed(cols)
+    W = (torch.randn((rows, cols), generator=g) * 0.02).to(dtype).to(gpu_device)
+    nrm = synth.make_norms(cols, "cpu", 3).to(gpu_device)
+    for alpha, n_prune in ((1.0, cols // 2), (0.5, cols // 3)):
+        Wc = W.clone()
+        want, want_mask = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), "cols", "cols", alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(Wc, nrm, "cols", "cols", alpha, n_prune, mask_out=mask)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), first_mismatch(Wc, want)
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
