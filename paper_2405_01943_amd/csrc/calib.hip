@@ -546,6 +546,281 @@ __global__ __launch_bounds__(256) void calib_pipe_kernel(
     }
 }
 
+// ------------------------------------------------- bf16 MFMA, 128-byte rows --
+// The same workgroup tile, wavefront tiles, MFMA order and epilogue as calib_pipe_kernel, with
+// K slabs of 64 columns: a wave-load covers 8 tile rows x 128 bytes, so every request to L2 is a
+// whole 128-byte line (half as many requests as with 64-byte row pieces, measured +9 % at the
+// same board power), and there is one barrier per 64 columns instead of one per 32.
+//
+// 64 KB per slab leaves room for 2.5 slabs in the 160 KB of LDS, so the A part (X: 256 rows x
+// 128 B) and the B part (Wgate and Wup: 2 x 128 rows x 128 B) of a slab are ring units of their
+// own, five units of 32 KB: slab s keeps its A part in unit 2 s mod 5 and its B part in unit
+// (2 s + 1) mod 5.  Both are free once every wavefront holds its last fragments of slab s, i.e.
+// after the barrier that follows K step 2 of 4; what goes into them is the B part of slab s + 2
+// (due one slab later) and the A part of slab s + 3 (due two slabs later), one wave-load every
+// second MFMA pair, the B part first.
+constexpr int P64_LDS = 5 * 32768;
+
+template <int ACT>
+__global__ __launch_bounds__(256) void calib_pipe64_kernel(
+    const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
+    const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
+    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+{
+    constexpr int BM = P_BM, BN = P_BN, BK = 64, WN = 2;
+    constexpr int TM = 128, TN = 64, MI = 4, NI = 2;
+    constexpr int CH = BK / 8;               // 16-byte chunks per tile row
+    constexpr int UNIT = 32768;              // A part, or gate half + up half of the B part
+    constexpr int B_HALF = BN * BK * 2;      // 16 KB
+    constexpr int A_WL = 8, B_WL = 4;        // wave-loads (8 rows x 128 B) per wavefront per slab: 8 + 4 + 4
+
+    extern __shared__ __attribute__((aligned(1024))) char lds64[];   // P64_LDS bytes
+
+    // ---- tile assignment: as in calib_pipe_kernel
+    constexpr int PT = 4, PN = 8;
+    const int64_t np_n = (tiles_n + PN - 1) / PN;
+    const int64_t idx = blockIdx.x / 8, within = idx % (PT * PN);
+    const int64_t patch = (idx / (PT * PN)) * 8 + blockIdx.x % 8;
+    const int64_t sr = patch / (np_n * super_rows), rem = patch % (np_n * super_rows);
+    const int64_t prow = sr * super_rows + rem % super_rows, pcol = rem / super_rows;
+    const int64_t tile_t = prow * PT + within / PN, tile_n = pcol * PN + within % PN;
+    if (tile_t >= tiles_t || tile_n >= tiles_n)
+        return;
+    const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- global -> LDS.  Lane l of a wave-load fills slot (l % 8) of row (l / 8) of an 8-row
+    // block, i.e. it fetches K chunk (l % 8) ^ swizzle of that row.  Rows past the end of the
+    // matrix are clamped; raw buffers bound every read, as in calib_pipe_kernel.
+    const int wl_row = lane >> 3, wl_slot = lane & 7;
+    const int64_t rows_x = T - t0 < BM ? T - t0 : BM, rows_w = d_int - n0 < BN ? d_int - n0 : BN;
+    uint32_t a_off[A_WL], b_off[B_WL];
+#pragma unroll
+    for (int p = 0; p < A_WL; ++p) {
+        const int r = (wave * A_WL + p) * 8 + wl_row;
+        const int64_t rr = r < rows_x ? r : rows_x - 1;
+        a_off[p] = (uint32_t)(rr * ldx * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
+    }
+#pragma unroll
+    for (int p = 0; p < B_WL; ++p) {
+        const int r = (wave * B_WL + p) * 8 + wl_row;
+        const int64_t rr = r < rows_w ? r : rows_w - 1;
+        b_off[p] = (uint32_t)(rr * ldw * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
+    }
+    constexpr int kRawBuffer = 0x00020000;
+    const int span_x = (int)((rows_x - 1) * ldx * 2 + d * 2), span_w = (int)((rows_w - 1) * ldw * 2 + d * 2);
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(X + t0 * ldx), 0, span_x, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rg =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wg + n0 * ldw), 0, span_w, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t ru =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wu + n0 * ldw), 0, span_w, kRawBuffer);
+
+    // q-th of this wavefront's 8 loads of an A part (slab at byte offset kb) into ring unit `unit`
+    auto issue_a = [&](int unit, int kb, int q) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(lds64 + unit * UNIT + (wave * A_WL + q) * 1024), 16,
+                                                 a_off[q], kb, 0, 0);
+    };
+    // q-th of its 8 loads of a B part: 4 of Wgate, then 4 of Wup
+    auto issue_b = [&](int unit, int kb, int q) {
+        if (q < B_WL)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rg, (lds_ptr_t)(lds64 + unit * UNIT + (wave * B_WL + q) * 1024), 16,
+                                                     b_off[q], kb, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                ru, (lds_ptr_t)(lds64 + unit * UNIT + B_HALF + (wave * B_WL + q - B_WL) * 1024), 16, b_off[q - B_WL], kb, 0, 0);
+    };
+
+    f32x16 acc_g[MI][NI], acc_u[MI][NI];
+
+    // ---- LDS -> registers.  A lane holds tile row (lane % 32) and K chunk kk * 2 + lane / 32 of
+    // K step kk (0..3); kk * 2 and lane / 32 occupy different bits, so the byte offset inside a
+    // unit is that of K step 0 XOR kk * 32.
+    const int fr = lane & 31, fc = lane >> 5;
+    int a_frag[MI], b_frag[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int r = wm * TM + i * 32 + fr;
+        a_frag[i] = (r * CH + swizzle<CH>(r, fc)) * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int r = wn * TN + j * 32 + fr;
+        b_frag[j] = (r * CH + swizzle<CH>(r, fc)) * 16;
+    }
+    struct Frags {
+        bf16x8 a[MI], g[NI], u[NI];
+    };
+    // q-th fragment of K step kk of the slab in units (ua, ub), in the order the MFMAs need them
+    auto read_one = [&](Frags &f, int ua, int ub, int kk, int q) {
+        const char *pa = lds64 + ua * UNIT, *pb = lds64 + ub * UNIT;
+        const int x = kk * 32;
+        switch (q) {
+        case 0: f.a[0] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[0] ^ x)); break;
+        case 1: f.g[0] = *reinterpret_cast<const bf16x8 *>(pb + (b_frag[0] ^ x)); break;
+        case 2: f.u[0] = *reinterpret_cast<const bf16x8 *>(pb + B_HALF + (b_frag[0] ^ x)); break;
+        case 3: f.g[1] = *reinterpret_cast<const bf16x8 *>(pb + (b_frag[1] ^ x)); break;
+        case 4: f.u[1] = *reinterpret_cast<const bf16x8 *>(pb + B_HALF + (b_frag[1] ^ x)); break;
+        case 5: f.a[1] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[1] ^ x)); break;
+        case 6: f.a[2] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[2] ^ x)); break;
+        default: f.a[3] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[3] ^ x)); break;
+        }
+    };
+    auto mfma_pair = [&](const Frags &f, int q) {
+        const int i = q >> 1, j = q & 1;
+        acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
+        acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
+    };
+
+    // ---- prologue: A0 B0 A1 B1 A2 fill the five units
+    const int S = (int)(d / BK);   // slabs; the host guarantees d % 64 == 0
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        issue_a(0, 0, q);
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        issue_b(1, 0, q);
+    if (S > 1) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            issue_a(2, BK * 2, q);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            issue_b(3, BK * 2, q);
+    }
+    if (S > 2) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            issue_a(4, 2 * BK * 2, q);
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc_g[i][j][r] = 0.0f;
+                acc_u[i][j][r] = 0.0f;
+            }
+    if (S > 2)
+        wait_vmcnt<24>();   // slab 0 has landed
+    else if (S > 1)
+        wait_vmcnt<16>();
+    else
+        wait_vmcnt<0>();
+    block_barrier();
+    Frags f0, f1;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        read_one(f0, 0, 1, 0, q);
+
+    // ---- main loop.  One slab = 4 K steps of 8 gate/up MFMA pairs, alternately on f0 and f1;
+    // the first pairs of a K step carry the fragment reads of the next one (2 2 1 1 1 1 per
+    // pair).  Between the barrier of slab s - 1 and that of slab s a wavefront issues the B part
+    // of slab s + 1 (K step 3 of slab s - 1, K step 0 of slab s) and the A part of slab s + 2
+    // (K steps 1 and 2).  B1, A2, B2: whether these parts exist and were not issued by the
+    // prologue; NEXT: whether a slab follows.  All four are compile-time, so the steady state
+    // has no branch between its MFMAs.
+    int ua = 0, ub = 1;   // ring units of slab s
+    constexpr int first_read[9] = {0, 2, 4, 5, 6, 7, 8, 8, 8};
+    auto slab_body = [&](int s, auto b1_tag, auto a2_tag, auto b2_tag, auto next_tag) {
+        constexpr bool B1 = decltype(b1_tag)::value, A2 = decltype(a2_tag)::value, B2 = decltype(b2_tag)::value,
+                       NEXT = decltype(next_tag)::value;
+        const int ua1 = ua + 2 >= 5 ? ua - 3 : ua + 2, ub1 = ub + 2 >= 5 ? ub - 3 : ub + 2;   // units of slab s + 1
+        const int uam = ua >= 2 ? ua - 2 : ua + 3, ubm = ub >= 2 ? ub - 2 : ub + 3;           // units of slab s - 1
+        const int k1 = (s + 1) * BK * 2, k2 = (s + 2) * BK * 2;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {   // K step 0
+            if (B1 && (q & 1) == 0)
+                issue_b(uam, k1, 4 + (q >> 1));
+#pragma unroll
+            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
+                read_one(f1, ua, ub, 1, r);
+            mfma_pair(f0, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {   // K step 1
+            if (A2 && (q & 1) == 0)
+                issue_a(ubm, k2, q >> 1);
+#pragma unroll
+            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
+                read_one(f0, ua, ub, 2, r);
+            mfma_pair(f1, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {   // K step 2
+            if (A2 && (q & 1) == 0)
+                issue_a(ubm, k2, 4 + (q >> 1));
+#pragma unroll
+            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
+                read_one(f1, ua, ub, 3, r);
+            mfma_pair(f0, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // Slab s + 1 has landed (only the A part of slab s + 2, the last 8 loads, may be in
+        // flight) and this wavefront holds its last fragments of slab s: vmcnt(8 or 0), lgkmcnt(0).
+        if (A2)
+            __builtin_amdgcn_s_waitcnt(0x0078);
+        else
+            __builtin_amdgcn_s_waitcnt(0x0070);
+        block_barrier();
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {   // K step 3; the units of slab s are free
+            if (B2 && (q & 1) == 0)
+                issue_b(ua, k2, q >> 1);
+            if (NEXT) {
+#pragma unroll
+                for (int r = first_read[q]; r < first_read[q + 1]; ++r)
+                    read_one(f0, ua1, ub1, 0, r);
+            }
+            mfma_pair(f1, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        ua = ua1;
+        ub = ub1;
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    if (S >= 3) {
+        slab_body(0, No{}, No{}, Yes{}, Yes{});   // B1 and A2 went out in the prologue
+        int s = 1;
+        for (; s + 2 < S; ++s)
+            slab_body(s, Yes{}, Yes{}, Yes{}, Yes{});
+        slab_body(s, Yes{}, No{}, No{}, Yes{});       // slab S - 2
+        slab_body(s + 1, No{}, No{}, No{}, No{});     // slab S - 1
+    } else if (S == 2) {
+        slab_body(0, No{}, No{}, No{}, Yes{});
+        slab_body(1, No{}, No{}, No{}, No{});
+    } else {
+        slab_body(0, No{}, No{}, No{}, No{});
+    }
+
+    // ---- epilogue: as in calib_mfma_kernel above
+    const bool full_t = t0 + BM <= T;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        float part = 0.0f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
+                const int64_t t = t0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
+                part += (full_t || t < T) ? y * y : 0.0f;
+            }
+        }
+        part += __shfl_xor(part, 32, 64);
+        const int64_t n = n0 + wn * TN + j * 32 + fr;
+        if (fc == 0 && n < d_int)
+            atomicAdd(sumsq + n, part);
+    }
+}
+
 // ------------------------------------------------------------------ f32 tiled --
 constexpr int F_BM = 64, F_BN = 64, F_BK = 16, F_PAD = 4;
 
@@ -677,6 +952,41 @@ static void launch_pipe(int act, dim3 grid, hipStream_t stream, const uint16_t *
     }
 }
 
+template <int ACT>
+static hipError_t launch_pipe64_act(dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
+                                    const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
+                                    float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+{
+    // the kernel's ring takes all 160 KB of LDS, more than a launch gets without asking
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(calib_pipe64_kernel<ACT>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, P64_LDS);
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL((calib_pipe64_kernel<ACT>), grid, dim3(256), P64_LDS, stream, X, T, ldx, Wg, Wu, ldw, d, d_int,
+                       sumsq, tiles_t, tiles_n, super_rows);
+    return hipSuccess;
+}
+
+static hipError_t launch_pipe64(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
+                                const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
+                                float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+{
+    switch (act) {
+    case DASS_ACT_SILU:
+        return launch_pipe64_act<DASS_ACT_SILU>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n,
+                                                super_rows);
+    case DASS_ACT_GELU_TANH:
+        return launch_pipe64_act<DASS_ACT_GELU_TANH>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t,
+                                                     tiles_n, super_rows);
+    case DASS_ACT_GELU_ERF:
+        return launch_pipe64_act<DASS_ACT_GELU_ERF>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t,
+                                                    tiles_n, super_rows);
+    default:
+        return launch_pipe64_act<DASS_ACT_RELU>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n,
+                                                super_rows);
+    }
+}
+
 }  // namespace dass
 
 extern "C" size_t dass_calib_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt)
@@ -743,7 +1053,15 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         const int64_t pipe_blocks = (patches + 7) / 8 * 8 * 32;
         if (pipe_ok && pipe_blocks > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
-        if (pipe_ok)
+        if (pipe_ok && d % 64 == 0) {   // 128-byte row pieces: calib_pipe64_kernel
+            const hipError_t e = launch_pipe64((int)act, dim3((unsigned)pipe_blocks), stream,
+                                               static_cast<const uint16_t *>(X), T, ldx,
+                                               static_cast<const uint16_t *>(Wgate),
+                                               static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq, tiles_t,
+                                               tiles_n, super_rows);
+            if (e != hipSuccess)
+                return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
+        } else if (pipe_ok)
             launch_pipe((int)act, dim3((unsigned)pipe_blocks), stream, static_cast<const uint16_t *>(X), T, ldx,
                         static_cast<const uint16_t *>(Wgate), static_cast<const uint16_t *>(Wup), ldw, d,
                         d_int, sumsq, tiles_t, tiles_n, super_rows);
