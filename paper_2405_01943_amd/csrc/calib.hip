@@ -35,12 +35,15 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // one 16-byte chun
 template <int ACT>
 __device__ __forceinline__ float glu_act_fast(float g)
 {
+    // exp2 and the reciprocal are the hardware's 1-ulp instructions; a true division costs a
+    // dozen instructions per element and the bf16 path is good to 1e-6 without it.
     if constexpr (ACT == DASS_ACT_SILU) {
-        return __fdividef(g, 1.0f + __expf(-g));
+        return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
     } else if constexpr (ACT == DASS_ACT_GELU_TANH) {
         // 0.5 g (1 + tanh z) = g / (1 + exp(-2 z)),  z = sqrt(2/pi) (g + 0.044715 g^3)
-        const float z2 = 1.5957691216057308f * g * (1.0f + 0.044715f * g * g);
-        return __fdividef(g, 1.0f + __expf(-z2));
+        // exp(-2 z) = exp2(g (c0 + c1 g^2)),  c0 = -2 sqrt(2/pi) log2(e),  c1 = 0.044715 c0
+        const float e = g * fmaf(-0.10294324f, g * g, -2.3022082f);
+        return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(e));
     } else if constexpr (ACT == DASS_ACT_GELU_ERF) {
         return 0.5f * g * (1.0f + erff(g * 0.7071067811865476f));
     } else {
@@ -800,8 +803,10 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
         slab_body(0, No{}, No{}, No{}, No{});
     }
 
-    // ---- epilogue: as in calib_mfma_kernel above
-    const bool full_t = t0 + BM <= T;
+    // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens (tokens are the
+    // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  One code path for
+    // whole and ragged tiles: a second, maskless copy of this loop nest measured slower overall.
+    const int valid = t0 + BM <= T ? BM : (int)(T - t0);   // tokens of this tile that exist
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         float part = 0.0f;
@@ -810,8 +815,8 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
-                const int64_t t = t0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
-                part += (full_t || t < T) ? y * y : 0.0f;
+                const int t = wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
+                part += t < valid ? y * y : 0.0f;
             }
         }
         part += __shfl_xor(part, 32, 64);
