@@ -54,6 +54,10 @@ def _load():
         lib.oracle_mask_nm.argtypes = [vp, i64, i64, i64, vp, ci, ci, ci, ci, vp]
         lib.oracle_mask_unstructured.restype = ci
         lib.oracle_mask_unstructured.argtypes = [vp, i64, i64, i64, vp, ci, ci, i64, vp]
+        lib.oracle_mlp_forward.restype = None
+        lib.oracle_mlp_forward.argtypes = [vp, i64, i64, vp, vp, i64, vp, i64, i64, i64, ci, vp, i64, vp, vp]
+        lib.oracle_compress_24.restype = i64
+        lib.oracle_compress_24.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64]
         lib.oracle_num_threads.restype = ci
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -189,3 +193,48 @@ def mask_unstructured(W, norms32, norm_axis: str, group_axis: str, alpha: float,
     if rc != 0:
         raise ValueError("oracle_mask_unstructured rejected the arguments")
     return W, mask
+
+
+def mlp_forward(X, Wg, Wu, Wd, kind: str, tokens=None, want_abs: bool = False):
+    """Eq. 2 then Eq. 3 in float64: out[t, :] = (sigma(x_t Wg^T) * (x_t Wu^T)) Wd^T.
+
+    ``tokens`` restricts the computation to the listed rows of X.  With ``want_abs`` also returns
+    sum_i |y_i Wd[j, i]| per output, the scale of the sum's rounding error.
+    """
+    X, Wg, Wu, Wd = _f32_2d(X, "X"), _f32_2d(Wg, "Wg"), _f32_2d(Wu, "Wu"), _f32_2d(Wd, "Wd")
+    T, d = X.shape
+    d_int = Wg.shape[0]
+    if Wg.shape != Wu.shape or Wg.shape[1] != d or _ld(Wg) != _ld(Wu) or Wd.shape != (d, d_int):
+        raise ValueError("shape mismatch between X, Wg, Wu, Wd")
+    if tokens is not None:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+        if tokens.size and (tokens.min() < 0 or tokens.max() >= T):
+            raise ValueError("token index out of range")
+    n = T if tokens is None else tokens.size
+    out = np.empty((n, d), dtype=np.float64)
+    absout = np.empty((n, d), dtype=np.float64) if want_abs else None
+    _load().oracle_mlp_forward(_ptr(X), T, _ld(X), _ptr(Wg), _ptr(Wu), _ld(Wg), _ptr(Wd), _ld(Wd),
+                               d, d_int, ACT[kind], None if tokens is None else _ptr(tokens), n,
+                               _ptr(out), None if absout is None else _ptr(absout))
+    return (out, absout) if want_abs else out
+
+
+def compress_24(W, group_axis: str):
+    """2:4 compressed form of W along ``group_axis``: (values float32, meta uint8, surplus groups).
+
+    values is [rows, cols/2] (cols) or [rows/2, cols] (rows); meta holds one nibble p0 | p1 << 2
+    per group, [rows, cols/8] or [rows/4, ceil(cols/2)].
+    """
+    W = _f32_2d(W, "W")
+    rows, cols = W.shape
+    if group_axis == "cols":
+        values = np.zeros((rows, cols // 2), dtype=np.float32)
+        meta = np.zeros((rows, cols // 8), dtype=np.uint8)
+    else:
+        values = np.zeros((rows // 2, cols), dtype=np.float32)
+        meta = np.zeros((rows // 4, (cols + 1) // 2), dtype=np.uint8)
+    rc = _load().oracle_compress_24(_ptr(W), rows, cols, _ld(W), AXIS[group_axis],
+                                    _ptr(values), values.shape[1], _ptr(meta), meta.shape[1])
+    if rc < 0:
+        raise ValueError("oracle_compress_24 rejected the shape")
+    return values, meta, int(rc)

@@ -19,6 +19,10 @@
  *     scores of Eq. 4 / Eq. 5.
  *   - oracle_mask_unstructured    : Sec. 3 "Pruning Granularity".
  *   - oracle_input_sumsq          : Sec. 2.1 Eq. 1, the input-feature norms of the Wanda metric.
+ *   - oracle_mlp_forward          : Sec. 2.2 Eq. 2 followed by Eq. 3, the output of the MLP
+ *     block (with pruned weights: the next block's calibration input).
+ *   - oracle_compress_24          : the 2:4 pattern of Sec. 2.2 "N:M sparsity" stored as kept
+ *     values plus 2-bit positions (the form sparse matrix units consume).
  *
  * Inputs are float arrays holding exactly the values the GPU sees (a bf16
  * value widens to float without rounding); all arithmetic is double.  The
@@ -33,7 +37,9 @@
  * invariants, alpha = 0 magnitude pruning, the Wanda reduction of Eq. 5,
  * scale invariance, Gram-matrix closed forms for the norms, activation spot
  * values, chunk additivity; sums of squares of integers and a hand-worked Wanda selection for
- * the input norms).  No function here is "parity unpinned".
+ * the input norms; one-hot closed forms, a library matrix product and the identity with
+ * oracle_sumsq for the MLP output; a hand-worked example and the round trip for the compressed
+ * form).  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -276,6 +282,108 @@ int oracle_mask_unstructured(float *W, int64_t rows, int64_t cols, int64_t ld,
         free(v);
     }
     return 0;
+}
+
+/*
+ * Eq. 2 then Eq. 3 for selected tokens:  y_i = sigma(x . Wg_i) * (x . Wu_i),
+ * out_j = sum over i of y_i * Wd[j, i].
+ *   X  : [T, d] row-major, row stride ldx;  Wg, Wu : [d_int, d], row stride ldw;
+ *   Wd : [d, d_int] row-major, row stride ldd (Down-Proj, transposed as in Sec. 3)
+ *   tokens : n_sel row indices into X, or NULL for all T rows
+ *   out    : [n_sel, d] doubles, overwritten
+ *   absout : NULL, or [n_sel, d] doubles receiving sum_i |y_i * Wd[j, i]| (the scale against
+ *            which a lower-precision evaluation of the same sum is judged)
+ * All sums in double, i and j in natural order.
+ */
+void oracle_mlp_forward(const float *X, int64_t T, int64_t ldx,
+                        const float *Wg, const float *Wu, int64_t ldw,
+                        const float *Wd, int64_t ldd, int64_t d, int64_t d_int, int act,
+                        const int64_t *tokens, int64_t n_sel, double *out, double *absout)
+{
+    const int64_t n = tokens ? n_sel : T;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < n; ++k) {
+        const float *x = X + (tokens ? tokens[k] : k) * ldx;
+        double *y = (double *)malloc((size_t)d_int * sizeof(double));
+        for (int64_t i = 0; i < d_int; ++i) {
+            const float *wg = Wg + i * ldw, *wu = Wu + i * ldw;
+            double g = 0.0, u = 0.0;
+            for (int64_t j = 0; j < d; ++j) {
+                g += (double)x[j] * (double)wg[j];
+                u += (double)x[j] * (double)wu[j];
+            }
+            y[i] = oracle_act(g, act) * u;
+        }
+        for (int64_t j = 0; j < d; ++j) {
+            const float *wd = Wd + j * ldd;
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t i = 0; i < d_int; ++i) {
+                const double term = y[i] * (double)wd[i];
+                acc += term;
+                aacc += fabs(term);
+            }
+            out[k * d + j] = acc;
+            if (absout)
+                absout[k * d + j] = aacc;
+        }
+        free(y);
+    }
+}
+
+/*
+ * 2:4 compressed form.  W is [rows, cols] row-major with row stride ld; groups are 4 consecutive
+ * positions along group_axis, aligned to multiples of 4.  A group's two stored positions are the
+ * first two entries of the list (positions holding a nonzero, ascending) followed by (positions
+ * holding a zero, ascending), put in ascending order p0 < p1; so a group with at most two
+ * nonzeros is represented exactly.  Its code is the nibble p0 | p1 << 2.
+ *   group_axis = cols: values [rows, cols / 2], row stride ldv: group g of row r fills
+ *                      values[r, 2 g] and values[r, 2 g + 1]; meta [rows, cols / 8] bytes, row
+ *                      stride ldm: the code of group g is nibble (g & 1) of byte g / 2 of row r.
+ *   group_axis = rows: values [rows / 2, cols]: group g of column c fills values[2 g, c] and
+ *                      values[2 g + 1, c]; meta [rows / 4, (cols + 1) / 2] bytes: the code of
+ *                      group g of column c is nibble (c & 1) of byte c / 2 of row g.
+ * Returns the number of groups that held more than two nonzeros (their surplus is dropped), or
+ * -1 for a bad shape.
+ */
+int64_t oracle_compress_24(const float *W, int64_t rows, int64_t cols, int64_t ld, int group_axis,
+                           float *values, int64_t ldv, uint8_t *meta, int64_t ldm)
+{
+    const int64_t len = group_axis == AXIS_ROWS ? rows : cols;
+    const int64_t lines = group_axis == AXIS_ROWS ? cols : rows;
+    if (rows <= 0 || cols <= 0 || len % 4 != 0 || (group_axis == AXIS_COLS && cols % 8 != 0))
+        return -1;
+    int64_t surplus = 0;
+    for (int64_t line = 0; line < lines; ++line) {
+        for (int64_t g = 0; g < len / 4; ++g) {
+            float w[4];
+            int order[4], n = 0, nz = 0;
+            for (int a = 0; a < 4; ++a)
+                w[a] = group_axis == AXIS_ROWS ? W[(4 * g + a) * ld + line] : W[line * ld + 4 * g + a];
+            for (int a = 0; a < 4; ++a)
+                if (w[a] != 0.0f)
+                    order[n++] = a, ++nz;
+            for (int a = 0; a < 4; ++a)
+                if (w[a] == 0.0f)
+                    order[n++] = a;
+            if (nz > 2)
+                ++surplus;
+            const int p0 = order[0] < order[1] ? order[0] : order[1];
+            const int p1 = order[0] < order[1] ? order[1] : order[0];
+            const uint8_t code = (uint8_t)(p0 | (p1 << 2));
+            if (group_axis == AXIS_ROWS) {
+                values[(2 * g) * ldv + line] = w[p0];
+                values[(2 * g + 1) * ldv + line] = w[p1];
+                uint8_t *b = meta + g * ldm + (line >> 1);
+                *b = (line & 1) ? (uint8_t)((*b & 0x0f) | (code << 4)) : (uint8_t)((*b & 0xf0) | code);
+            } else {
+                values[line * ldv + 2 * g] = w[p0];
+                values[line * ldv + 2 * g + 1] = w[p1];
+                uint8_t *b = meta + line * ldm + (g >> 1);
+                *b = (g & 1) ? (uint8_t)((*b & 0x0f) | (code << 4)) : (uint8_t)((*b & 0xf0) | code);
+            }
+        }
+    }
+    return surplus;
 }
 
 /* Number of OpenMP threads the loops above will use (for the baseline report). */
