@@ -211,6 +211,68 @@ dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, in
                                          void *hip_stream);
 
 /* Name of a status code; never NULL. */
+/*
+ * The output of the MLP block (Sec. 2.2 Eq. 2 followed by Eq. 3):
+ *
+ *   y[t, i]   = act(x_t . Wgate_i) * (x_t . Wup_i)
+ *   out[t, j] = sum_i y[t, i] * Wdown[j, i]
+ *
+ * With pruned weights this is the input the next block is calibrated on when
+ * blocks are pruned one after the other.
+ *
+ *   X      [T, d] row stride ldx;  Wgate, Wup [d_int, d] row stride ldw;
+ *   Wdown  [d, d_int] row stride ldd;  all device, read only
+ *   out    [T, d] row stride ldo, device, overwritten
+ *   workspace  device scratch of at least dass_mlp_forward_workspace_bytes()
+ *          bytes, 16-byte aligned: y, [T, d_int] in dtype dt (callers short of
+ *          memory split the tokens: rows are independent)
+ * dt: DASS_BF16 only (DASS_ERR_DTYPE otherwise).  Products accumulate in f32;
+ * y is rounded to bf16 once (round to nearest even), out once.  d and d_int
+ * must be multiples of 64 (DASS_ERR_SHAPE), pointers 16-byte aligned and
+ * leading dimensions multiples of 8 (DASS_ERR_ALIGN).  Two launches on
+ * hip_stream; nothing is allocated.
+ */
+size_t dass_mlp_forward_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt);
+
+dass_status dass_mlp_forward(const void *X, int64_t T, int64_t ldx, const void *Wgate,
+                             const void *Wup, int64_t ldw, const void *Wdown, int64_t ldd,
+                             int64_t d, int64_t d_int, dass_dtype dt, dass_act act, void *out,
+                             int64_t ldo, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/*
+ * The 2:4 pattern (Sec. 2.2 "N:M sparsity" with N = 2, M = 4) in compressed
+ * form: per group of 4 consecutive positions along group_axis, two values
+ * and their two 2-bit positions, which is what sparse matrix units read.
+ *
+ * A group's stored positions are the first two entries of (positions holding
+ * a nonzero, ascending) followed by (positions holding a zero, ascending),
+ * in ascending order p0 < p1; its code is the nibble p0 | p1 << 2.  A matrix
+ * with at most two nonzeros per group is represented exactly (-0 counts as
+ * zero).
+ *
+ *   W      [rows, cols] row stride ld, dtype dt, device, read only
+ *   group_axis = DASS_AXIS_COLS: values_out [rows, cols / 2] row stride ldv:
+ *          group g of row r fills values[r, 2 g] and [r, 2 g + 1];
+ *          meta_out [rows, cols / 8] bytes, row stride ldm: the code of group
+ *          g is nibble (g & 1) of byte g / 2 of row r.  cols % 8 == 0; ldv a
+ *          multiple of 4 elements, ldm any.
+ *   group_axis = DASS_AXIS_ROWS: values_out [rows / 2, cols]: group g of
+ *          column c fills values[2 g, c] and [2 g + 1, c]; meta_out
+ *          [rows / 4, cols / 2] bytes: the code of group g of column c is
+ *          nibble (c & 1) of byte c / 2 of row g.  rows % 4 == 0, cols % 8 == 0;
+ *          ldv a multiple of 8 (bf16) / 4 (f32) elements, meta_out 4-byte
+ *          aligned and ldm a multiple of 4.
+ *   values_out  dtype dt, device, 16-byte aligned; must not overlap W
+ *   meta_out    device
+ *   surplus_out NULL, or one device int64 to which the number of groups that
+ *          held more than two nonzeros is ADDED (their surplus is dropped)
+ */
+dass_status dass_compress_24(const void *W, int64_t rows, int64_t cols, int64_t ld, dass_dtype dt,
+                             dass_axis group_axis, void *values_out, int64_t ldv,
+                             uint8_t *meta_out, int64_t ldm, long long *surplus_out,
+                             void *hip_stream);
+
 const char *dass_status_string(dass_status s);
 /* Detail of the calling thread's most recent failed call ("" if none). */
 const char *dass_last_error_string(void);

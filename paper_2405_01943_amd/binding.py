@@ -26,6 +26,7 @@ EXPORTS = (
     "dass_nm_batched_workspace_bytes", "dass_score_mask_nm_batched",
     "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
     "dass_input_norms_workspace_bytes", "dass_input_norms",
+    "dass_mlp_forward_workspace_bytes", "dass_mlp_forward", "dass_compress_24",
     "dass_status_string", "dass_last_error_string", "dass_version",
 )
 
@@ -87,6 +88,13 @@ def load_library() -> ctypes.CDLL:
     lib.dass_input_norms_workspace_bytes.argtypes = [i64, i64]
     lib.dass_input_norms.restype = ci
     lib.dass_input_norms.argtypes = [vp, i64, i64, i64, ci, vp, ci, vp, vp, sz, vp]
+    lib.dass_mlp_forward_workspace_bytes.restype = sz
+    lib.dass_mlp_forward_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.dass_mlp_forward.restype = ci
+    lib.dass_mlp_forward.argtypes = [vp, i64, i64, vp, vp, i64, vp, i64, i64, i64, ci, ci, vp, i64,
+                                     vp, sz, vp]
+    lib.dass_compress_24.restype = ci
+    lib.dass_compress_24.argtypes = [vp, i64, i64, i64, ci, ci, vp, i64, vp, i64, vp, vp]
     lib.dass_status_string.restype = ctypes.c_char_p
     lib.dass_status_string.argtypes = [ci]
     lib.dass_last_error_string.restype = ctypes.c_char_p
@@ -176,6 +184,32 @@ def input_norms(X: torch.Tensor, sumsq: torch.Tensor, accumulate: bool = False,
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.dass_input_norms(_ptr(X), T, ldx, d, DTYPE[X.dtype], _ptr(sumsq), int(bool(accumulate)),
                                 _ptr(norms_out), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def mlp_forward_workspace_bytes(T: int, d: int, d_int: int, dtype=torch.bfloat16) -> int:
+    return int(load_library().dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[dtype]))
+
+
+def mlp_forward(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, Wdown: torch.Tensor, act: str,
+                out: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_mlp_forward: out = (act(X Wgate^T) * (X Wup^T)) Wdown^T (Eq. 2 then Eq. 3)."""
+    lib = load_library()
+    T, d, ldx = _matrix(X, "X")
+    d_int, d2, ldw = _matrix(Wgate, "Wgate")
+    if _matrix(Wup, "Wup") != (d_int, d2, ldw) or d2 != d:
+        raise ValueError("Wgate and Wup must be [d_int, d] with one leading dimension")
+    dd, di, ldd = _matrix(Wdown, "Wdown")
+    To, do, ldo = _matrix(out, "out")
+    if (dd, di) != (d, d_int) or (To, do) != (T, d):
+        raise ValueError("Wdown must be [d, d_int] and out [T, d]")
+    if len({X.dtype, Wgate.dtype, Wup.dtype, Wdown.dtype, out.dtype}) != 1:
+        raise TypeError("X, the weights and out must share one dtype")
+    if workspace is None:
+        workspace = _scratch(int(lib.dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[X.dtype])), X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.dass_mlp_forward(_ptr(X), T, ldx, _ptr(Wgate), _ptr(Wup), ldw, _ptr(Wdown), ldd, d, d_int,
+                                DTYPE[X.dtype], ACT[act], _ptr(out), ldo, _ptr(workspace), ws_bytes,
+                                _stream(stream)))
 
 
 # ------------------------------------------------------------------ stage 2 --
@@ -280,3 +314,22 @@ def score_mask_unstructured(W: torch.Tensor, norms: torch.Tensor, norm_axis: str
                                             AXIS[norm_axis], AXIS[group_axis], float(alpha),
                                             int(n_prune), _ptr(mask_out), _ptr(workspace), ws_bytes,
                                             _stream(stream)))
+
+
+def compress_24(W: torch.Tensor, group_axis: str, values_out: torch.Tensor, meta_out: torch.Tensor,
+                surplus_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_compress_24: kept values and 2-bit position codes of a 2:4 sparse matrix."""
+    lib = load_library()
+    rows, cols, ld = _matrix(W, "W")
+    vr, vc, ldv = _matrix(values_out, "values_out")
+    if values_out.dtype != W.dtype or (vr, vc) != ((rows // 2, cols) if group_axis == "rows" else (rows, cols // 2)):
+        raise TypeError("values_out: need W's dtype and [rows / 2, cols] (rows) or [rows, cols / 2] (cols)")
+    want = (rows // 4, cols // 2) if group_axis == "rows" else (rows, cols // 8)
+    if meta_out.dtype != torch.uint8 or meta_out.dim() != 2 or tuple(meta_out.shape) != want or meta_out.stride(1) != 1:
+        raise TypeError(f"meta_out: need uint8 {want}")
+    ldm = meta_out.stride(0) if meta_out.shape[0] > 1 else max(meta_out.stride(0), meta_out.shape[1])
+    if surplus_out is not None and (surplus_out.dtype != torch.int64 or surplus_out.numel() != 1):
+        raise TypeError("surplus_out: need one int64")
+    _check(lib.dass_compress_24(_ptr(W), rows, cols, ld, DTYPE[W.dtype], AXIS[group_axis], _ptr(values_out), ldv,
+                                _ptr(meta_out), ldm, _ptr(surplus_out), _stream(stream)))
+

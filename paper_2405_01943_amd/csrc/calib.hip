@@ -562,15 +562,35 @@ __global__ __launch_bounds__(256) void calib_pipe_kernel(
 // after the barrier that follows K step 2 of 4; what goes into them is the B part of slab s + 2
 // (due one slab later) and the A part of slab s + 3 (due two slabs later), one wave-load every
 // second MFMA pair, the B part first.
+//
+// What happens to the finished tile is a template parameter:
+//   kEpiNorms  the calibration statistic: y = act(g) u squared and summed over the tokens
+//   kEpiGlu    Eq. 2 itself: y rounded to bf16 and stored, [T, d_int] row-major
+//   kEpiGemm   no activation: a plain product X W^T stored as bf16 (Eq. 3 with X = y, W = Wdown).
+//              The "gate" rows of a tile are W rows n0 .. n0 + 127, its "up" rows the next 128,
+//              so a tile is 256 x 256 outputs and Wu is not used.
+// The two storing forms go through LDS (free after the last barrier of the main loop): lanes
+// pair neighbouring columns into 32-bit words, the workgroup then writes whole 16-byte chunks
+// of output rows.
 constexpr int P64_LDS = 5 * 32768;
+enum { kEpiNorms = 0, kEpiGlu = 1, kEpiGemm = 2 };
 
-template <int ACT>
+// float -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+template <int ACT, int EPI>
 __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
     const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
-    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+    float *__restrict__ sumsq, uint16_t *__restrict__ out, int64_t ldo, int64_t tiles_t, int64_t tiles_n,
+    int super_rows)
 {
     constexpr int BM = P_BM, BN = P_BN, BK = 64, WN = 2;
+    constexpr int BN_TILE = EPI == kEpiGemm ? 2 * BN : BN;   // rows of W (output columns) per tile
     constexpr int TM = 128, TN = 64, MI = 4, NI = 2;
     constexpr int CH = BK / 8;               // 16-byte chunks per tile row
     constexpr int UNIT = 32768;              // A part, or gate half + up half of the B part
@@ -589,7 +609,7 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     const int64_t tile_t = prow * PT + within / PN, tile_n = pcol * PN + within % PN;
     if (tile_t >= tiles_t || tile_n >= tiles_n)
         return;
-    const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
+    const int64_t t0 = tile_t * BM, n0 = tile_n * BN_TILE;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -600,6 +620,10 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     // matrix are clamped; raw buffers bound every read, as in calib_pipe_kernel.
     const int wl_row = lane >> 3, wl_slot = lane & 7;
     const int64_t rows_x = T - t0 < BM ? T - t0 : BM, rows_w = d_int - n0 < BN ? d_int - n0 : BN;
+    // kEpiGemm: the second 128 rows of the tile may be fewer, or none (then an empty buffer:
+    // its reads fetch nothing and return 0; clamped rows beyond its end do the same)
+    const int64_t left_u = d_int - n0 - BN;
+    const int64_t rows_u = EPI != kEpiGemm ? rows_w : left_u < 0 ? 0 : left_u < BN ? left_u : BN;
     uint32_t a_off[A_WL], b_off[B_WL];
 #pragma unroll
     for (int p = 0; p < A_WL; ++p) {
@@ -615,12 +639,14 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     }
     constexpr int kRawBuffer = 0x00020000;
     const int span_x = (int)((rows_x - 1) * ldx * 2 + d * 2), span_w = (int)((rows_w - 1) * ldw * 2 + d * 2);
+    const int span_u = rows_u > 0 ? (int)((rows_u - 1) * ldw * 2 + d * 2) : 0;
+    const uint16_t *up_rows = EPI == kEpiGemm ? Wg + (n0 + BN) * ldw : Wu + n0 * ldw;
     const __amdgpu_buffer_rsrc_t rx =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(X + t0 * ldx), 0, span_x, kRawBuffer);
     const __amdgpu_buffer_rsrc_t rg =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wg + n0 * ldw), 0, span_w, kRawBuffer);
     const __amdgpu_buffer_rsrc_t ru =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wu + n0 * ldw), 0, span_w, kRawBuffer);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(up_rows), 0, span_u, kRawBuffer);
 
     // q-th of this wavefront's 8 loads of an A part (slab at byte offset kb) into ring unit `unit`
     auto issue_a = [&](int unit, int kb, int q) {
@@ -803,26 +829,70 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
         slab_body(0, No{}, No{}, No{}, No{});
     }
 
-    // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens (tokens are the
-    // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  One code path for
-    // whole and ragged tiles: a second, maskless copy of this loop nest measured slower overall.
-    const int valid = t0 + BM <= T ? BM : (int)(T - t0);   // tokens of this tile that exist
+    if constexpr (EPI == kEpiNorms) {
+        // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens (tokens are the
+        // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  One code path for
+        // whole and ragged tiles: a second, maskless copy of this loop nest measured slower overall.
+        const int valid = t0 + BM <= T ? BM : (int)(T - t0);   // tokens of this tile that exist
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        float part = 0.0f;
+        for (int j = 0; j < NI; ++j) {
+            float part = 0.0f;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
+            for (int i = 0; i < MI; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
-                const int t = wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
-                part += t < valid ? y * y : 0.0f;
+                for (int r = 0; r < 16; ++r) {
+                    const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
+                    const int t = wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
+                    part += t < valid ? y * y : 0.0f;
+                }
             }
+            part += __shfl_xor(part, 32, 64);
+            const int64_t n = n0 + wn * TN + j * 32 + fr;
+            if (fc == 0 && n < d_int)
+                atomicAdd(sumsq + n, part);
         }
-        part += __shfl_xor(part, 32, 64);
-        const int64_t n = n0 + wn * TN + j * 32 + fr;
-        if (fc == 0 && n < d_int)
-            atomicAdd(sumsq + n, part);
+    } else {
+        // ---- storing epilogues.  Every wavefront is past the last barrier and the last LDS read
+        // of the main loop, so the ring is free: the tile goes there as bf16, row stride SROW (16
+        // bytes of padding), and leaves it in whole 16-byte chunks of output rows.
+        constexpr int COLS = BN_TILE;                // output columns of the tile
+        constexpr int SROW = COLS * 2 + 16;
+        static_assert(BM * SROW <= P64_LDS, "the tile fits in the ring");
+        // A lane holds rows r and r + 1 (registers 2 k, 2 k + 1) of column fr; with its neighbour
+        // fr ^ 1 it trades one of them, so that even lanes own row 2 k and odd lanes row 2 k + 1
+        // of the column pair: one 32-bit LDS write each.
+        auto put_pair = [&](float v0, float v1, int row_even, int col_base) {
+            const bool odd = fr & 1;
+            const float mine = odd ? v1 : v0, send = odd ? v0 : v1;
+            const float got = __shfl_xor(send, 1, 64);
+            const uint32_t word = odd ? bf16_bits(got) | bf16_bits(mine) << 16 : bf16_bits(mine) | bf16_bits(got) << 16;
+            const int row = row_even + (odd ? 1 : 0), col = col_base + (fr & ~1);
+            *reinterpret_cast<uint32_t *>(lds64 + row * SROW + col * 2) = word;
+        };
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int row_even = wm * TM + i * 32 + 8 * (k / 2) + 4 * fc + 2 * (k % 2);
+                    const int col_base = wn * TN + j * 32;
+                    if constexpr (EPI == kEpiGlu) {
+                        put_pair(glu_act_fast<ACT>(acc_g[i][j][2 * k]) * acc_u[i][j][2 * k],
+                                 glu_act_fast<ACT>(acc_g[i][j][2 * k + 1]) * acc_u[i][j][2 * k + 1], row_even, col_base);
+                    } else {
+                        put_pair(acc_g[i][j][2 * k], acc_g[i][j][2 * k + 1], row_even, col_base);
+                        put_pair(acc_u[i][j][2 * k], acc_u[i][j][2 * k + 1], row_even, BN + col_base);
+                    }
+                }
+        __syncthreads();
+        constexpr int CPR = COLS / 8;   // 16-byte chunks per tile row
+        for (int c = tid; c < BM * CPR; c += 256) {
+            const int row = c / CPR, cc = c % CPR;
+            const int64_t t = t0 + row, n = n0 + cc * 8;
+            if (t < T && n < d_int)   // d_int is a multiple of 8: a chunk is inside or outside
+                *reinterpret_cast<u32x4 *>(out + t * ldo + n) = *reinterpret_cast<const u32x4 *>(lds64 + row * SROW + cc * 16);
+        }
     }
 }
 
@@ -957,39 +1027,51 @@ static void launch_pipe(int act, dim3 grid, hipStream_t stream, const uint16_t *
     }
 }
 
-template <int ACT>
+template <int ACT, int EPI>
 static hipError_t launch_pipe64_act(dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
                                     const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
-                                    float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+                                    float *sumsq, uint16_t *out, int64_t ldo, int64_t tiles_t, int64_t tiles_n,
+                                    int super_rows)
 {
     // the kernel's ring takes all 160 KB of LDS, more than a launch gets without asking
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(calib_pipe64_kernel<ACT>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(calib_pipe64_kernel<ACT, EPI>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, P64_LDS);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL((calib_pipe64_kernel<ACT>), grid, dim3(256), P64_LDS, stream, X, T, ldx, Wg, Wu, ldw, d, d_int,
-                       sumsq, tiles_t, tiles_n, super_rows);
+    hipLaunchKernelGGL((calib_pipe64_kernel<ACT, EPI>), grid, dim3(256), P64_LDS, stream, X, T, ldx, Wg, Wu, ldw, d,
+                       d_int, sumsq, out, ldo, tiles_t, tiles_n, super_rows);
     return hipSuccess;
 }
 
+template <int EPI>
 static hipError_t launch_pipe64(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
                                 const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
-                                float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
+                                float *sumsq, uint16_t *out, int64_t ldo, int64_t tiles_t, int64_t tiles_n,
+                                int super_rows)
 {
     switch (act) {
     case DASS_ACT_SILU:
-        return launch_pipe64_act<DASS_ACT_SILU>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n,
-                                                super_rows);
+        return launch_pipe64_act<DASS_ACT_SILU, EPI>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, out, ldo,
+                                                     tiles_t, tiles_n, super_rows);
     case DASS_ACT_GELU_TANH:
-        return launch_pipe64_act<DASS_ACT_GELU_TANH>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t,
-                                                     tiles_n, super_rows);
+        return launch_pipe64_act<DASS_ACT_GELU_TANH, EPI>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, out,
+                                                          ldo, tiles_t, tiles_n, super_rows);
     case DASS_ACT_GELU_ERF:
-        return launch_pipe64_act<DASS_ACT_GELU_ERF>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t,
-                                                    tiles_n, super_rows);
+        return launch_pipe64_act<DASS_ACT_GELU_ERF, EPI>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, out,
+                                                         ldo, tiles_t, tiles_n, super_rows);
     default:
-        return launch_pipe64_act<DASS_ACT_RELU>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, tiles_t, tiles_n,
-                                                super_rows);
+        return launch_pipe64_act<DASS_ACT_RELU, EPI>(grid, stream, X, T, ldx, Wg, Wu, ldw, d, d_int, sumsq, out, ldo,
+                                                     tiles_t, tiles_n, super_rows);
     }
+}
+
+// Grid of the pipelined kernels: whole 4 x 8 patches of tiles dealt to the 8 XCDs, rows of
+// patches in groups of `super_rows`.  Returns 0 when one launch cannot hold it.
+static int64_t pipe_grid(int64_t tiles_t, int64_t tiles_n, int super_rows)
+{
+    const int64_t patches = ((tiles_t + 3) / 4 + super_rows - 1) / super_rows * super_rows * ((tiles_n + 7) / 8);
+    const int64_t blocks = (patches + 7) / 8 * 8 * 32;
+    return blocks > 0x7fffffffLL ? 0 : blocks;
 }
 
 }  // namespace dass
@@ -1059,11 +1141,11 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         if (pipe_ok && pipe_blocks > 0x7fffffffLL)
             return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
         if (pipe_ok && d % 64 == 0) {   // 128-byte row pieces: calib_pipe64_kernel
-            const hipError_t e = launch_pipe64((int)act, dim3((unsigned)pipe_blocks), stream,
-                                               static_cast<const uint16_t *>(X), T, ldx,
-                                               static_cast<const uint16_t *>(Wgate),
-                                               static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq, tiles_t,
-                                               tiles_n, super_rows);
+            const hipError_t e = launch_pipe64<kEpiNorms>((int)act, dim3((unsigned)pipe_blocks), stream,
+                                                          static_cast<const uint16_t *>(X), T, ldx,
+                                                          static_cast<const uint16_t *>(Wgate),
+                                                          static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
+                                                          nullptr, 0, tiles_t, tiles_n, super_rows);
             if (e != hipSuccess)
                 return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
         } else if (pipe_ok)
@@ -1094,4 +1176,86 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         s = check_launch("sqrt kernel");
     }
     return s;
+}
+
+// ------------------------------------------------------------- MLP output --
+extern "C" size_t dass_mlp_forward_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt)
+{
+    (void)d;
+    if (T <= 0 || d_int <= 0 || dt != DASS_BF16)
+        return 0;
+    return (size_t)T * (size_t)d_int * 2;   // y of Eq. 2 as bf16, [T, d_int]
+}
+
+extern "C" dass_status dass_mlp_forward(const void *X, int64_t T, int64_t ldx, const void *Wgate, const void *Wup,
+                                        int64_t ldw, const void *Wdown, int64_t ldd, int64_t d, int64_t d_int,
+                                        dass_dtype dt, dass_act act, void *out, int64_t ldo, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_mlp_forward";
+    if (!X || !Wgate || !Wup || !Wdown || !out || !workspace)
+        return fail(DASS_ERR_NULL, "%s: X, Wgate, Wup, Wdown, out and workspace must not be NULL", fn);
+    if (!valid_dtype(dt))
+        return fail(DASS_ERR_DTYPE, "%s: unknown dtype %d", fn, (int)dt);
+    if (dt != DASS_BF16)
+        return fail(DASS_ERR_DTYPE, "%s: only bf16 is implemented", fn);
+    if ((int)act < DASS_ACT_SILU || (int)act > DASS_ACT_RELU)
+        return fail(DASS_ERR_DTYPE, "%s: unknown activation %d", fn, (int)act);
+    if (T <= 0 || d <= 0 || d_int <= 0)
+        return fail(DASS_ERR_SHAPE, "%s: T=%lld d=%lld d_int=%lld must be positive", fn, (long long)T,
+                    (long long)d, (long long)d_int);
+    if (d % 64 != 0 || d_int % 64 != 0)
+        return fail(DASS_ERR_SHAPE, "%s: d=%lld and d_int=%lld must be multiples of 64", fn, (long long)d,
+                    (long long)d_int);
+    if (ldx < d || ldw < d || ldd < d_int || ldo < d)
+        return fail(DASS_ERR_SHAPE, "%s: a leading dimension is shorter than its row", fn);
+    if (!aligned16(X) || !aligned16(Wgate) || !aligned16(Wup) || !aligned16(Wdown) || !aligned16(out) ||
+        !aligned16(workspace))
+        return fail(DASS_ERR_ALIGN, "%s: every pointer must be 16-byte aligned", fn);
+    if (ldx % 8 != 0 || ldw % 8 != 0 || ldd % 8 != 0 || ldo % 8 != 0)
+        return fail(DASS_ERR_ALIGN, "%s: leading dimensions must be multiples of 8 elements", fn);
+    if (workspace_bytes < dass_mlp_forward_workspace_bytes(T, d, d_int, dt))
+        return fail(DASS_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
+                    dass_mlp_forward_workspace_bytes(T, d, d_int, dt));
+    // 32-bit byte offsets inside a tile's rows, as in dass_calib_norms
+    if ((int64_t)P_BM * ldx * 2 >= 0x7fffffffLL || (int64_t)P_BN * ldw * 2 >= 0x7fffffffLL ||
+        (int64_t)P_BM * d_int * 2 >= 0x7fffffffLL || (int64_t)P_BN * ldd * 2 >= 0x7fffffffLL)
+        return fail(DASS_ERR_SHAPE, "%s: rows too long for the tile addressing", fn);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint16_t *Y = static_cast<uint16_t *>(workspace);
+    const int64_t tiles_t = (T + P_BM - 1) / P_BM;
+    // Eq. 2: y = act(X Wgate^T) * (X Wup^T), tiles of 256 tokens x 128 neurons
+    {
+        const int64_t tiles_n = (d_int + P_BN - 1) / P_BN;
+        const int super_rows = 2 * d_int * d * 2 > (256LL << 20) ? 8 : 1;
+        const int64_t blocks = pipe_grid(tiles_t, tiles_n, super_rows);
+        if (blocks == 0)
+            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+        const hipError_t e = launch_pipe64<kEpiGlu>((int)act, dim3((unsigned)blocks), stream,
+                                                    static_cast<const uint16_t *>(X), T, ldx,
+                                                    static_cast<const uint16_t *>(Wgate),
+                                                    static_cast<const uint16_t *>(Wup), ldw, d, d_int, nullptr, Y,
+                                                    d_int, tiles_t, tiles_n, super_rows);
+        if (e != hipSuccess)
+            return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
+        const dass_status s = check_launch("GLU kernel");
+        if (s != DASS_OK)
+            return s;
+    }
+    // Eq. 3: out = y Wdown^T, tiles of 256 tokens x 256 output features, K = d_int
+    {
+        const int64_t tiles_n = (d + 2 * P_BN - 1) / (2 * P_BN);
+        const int super_rows = d * d_int * 2 > (256LL << 20) ? 8 : 1;
+        const int64_t blocks = pipe_grid(tiles_t, tiles_n, super_rows);
+        if (blocks == 0)
+            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+        const hipError_t e = launch_pipe64_act<DASS_ACT_RELU, kEpiGemm>(
+            dim3((unsigned)blocks), stream, Y, T, d_int, static_cast<const uint16_t *>(Wdown), nullptr, ldd, d_int, d,
+            nullptr, static_cast<uint16_t *>(out), ldo, tiles_t, tiles_n, super_rows);
+        if (e != hipSuccess)
+            return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
+        return check_launch("down-projection kernel");
+    }
 }

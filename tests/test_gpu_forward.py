@@ -1,0 +1,93 @@
+"""GPU parity: dass_mlp_forward (Eq. 2 then Eq. 3, bf16) against the float64 oracle.
+
+Tolerance, derived from the arithmetic: y is rounded to bf16 once (relative error <= 2^-9 per
+term of the Eq. 3 sum), the output once (2^-9 of its value), sums accumulate in f32
+(K * 2^-24 <= 6.6e-4 of the terms' absolute sum at the worst, far less in practice).  With
+A = sum_i |y_i Wdown[j, i]| from the oracle:  |gpu - oracle| <= 2^-8 A + 2^-8 |oracle|,
+i.e. twice the two rounding bounds.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_01943_amd as dass
+from paper_2405_01943_amd import synth
+
+from gpu_helpers import padded, to_np32
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(out, ref, ab, what):
+    out = np.asarray(out, dtype=np.float64)
+    tol = 2.0 ** -8 * ab + 2.0 ** -8 * np.abs(ref) + 1e-30
+    err = np.abs(out - ref)
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, f"{what}: worst error / tolerance = {worst:.3f}"
+    # a systematic error (a dropped K slab, a wrong row) would sit near the bound everywhere;
+    # rounding noise averages far below it
+    assert float(np.mean(err / tol)) < 0.25, what
+    return worst
+
+
+@pytest.mark.parametrize("act", ["silu", "gelu_tanh", "relu", "gelu_erf"])
+@pytest.mark.parametrize("T,d,d_int,pad", [(300, 192, 320, 0), (513, 256, 448, 8), (256, 64, 64, 0), (70, 128, 704, 16)])
+def test_forward_small_shapes(gpu_device, act, T, d, d_int, pad):
+    g = torch.Generator(device="cpu").manual_seed(T + 7 * d + 13 * d_int)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(gpu_device)
+    Wg = (torch.randn((d_int, d), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    Wu = (torch.randn((d_int, d), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    Wd = (torch.randn((d, d_int), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    out = torch.full((T, d), 3.0, dtype=torch.bfloat16, device=gpu_device)
+    if pad:
+        X, Wd, out = padded(X, pad), padded(Wd, pad), padded(out, pad)
+        Wg = padded(Wg, pad)
+        Wu = padded(Wu, pad)
+    dass.mlp_forward(X, Wg, Wu, Wd, act, out)
+    torch.cuda.synchronize()
+    ref, ab = oracle.mlp_forward(to_np32(X), to_np32(Wg), to_np32(Wu), to_np32(Wd), act, want_abs=True)
+    _check(to_np32(out), ref, ab, f"{act} T={T} d={d} d_int={d_int}")
+    if pad:
+        assert torch.all(out._base[:, d:] == 7.0)   # nothing written past a row's end
+
+
+def test_forward_token_chunks_are_independent(gpu_device):
+    """Rows of the output depend on their own token only: two halves equal the whole, bit for bit."""
+    T, d, d_int = 700, 128, 256
+    g = torch.Generator(device="cpu").manual_seed(3)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(gpu_device)
+    Wg, Wu = ((torch.randn((d_int, d), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device) for _ in range(2))
+    Wd = (torch.randn((d, d_int), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    whole = torch.empty((T, d), dtype=torch.bfloat16, device=gpu_device)
+    parts = torch.empty_like(whole)
+    dass.mlp_forward(X, Wg, Wu, Wd, "silu", whole)
+    dass.mlp_forward(X[:300], Wg, Wu, Wd, "silu", parts[:300])
+    dass.mlp_forward(X[300:], Wg, Wu, Wd, "silu", parts[300:])
+    torch.cuda.synchronize()
+    assert torch.equal(whole.view(torch.int16), parts.view(torch.int16))
+
+
+def test_forward_full_size_with_pruned_weights(gpu_device):
+    """The LLaMA2-7B-shaped MLP with DaSS 2:4 weights on a 32768-token chunk of the calibration
+    set (the launch shape the benchmark times), checked on sampled tokens: all d outputs of the
+    first and last token, of both sides of tile boundaries and of seeded random ones."""
+    cfg = synth.CONFIGS["llama2_7b"]
+    dev = gpu_device
+    T, d, d_int = 32768, cfg.d, cfg.d_int
+    X = synth.make_x(cfg, 0, T, dev)
+    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
+    norms = synth.make_norms(d_int, dev)
+    dass.score_mask_nm(Wg, norms, "rows", "rows", 0.5, 2, 4)
+    dass.score_mask_nm(Wu, norms, "rows", "rows", 0.5, 2, 4)
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    out = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    dass.mlp_forward(X, Wg, Wu, Wd, cfg.act, out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    tokens = np.unique(np.concatenate([[0, 1, 255, 256, 257, 1023, 1024, T - 257, T - 256, T - 1],
+                                       rng.integers(0, T, size=14)]))
+    ref, ab = oracle.mlp_forward(to_np32(X[torch.as_tensor(tokens, device=dev)]), to_np32(Wg), to_np32(Wu),
+                                 to_np32(Wd), cfg.act, want_abs=True)
+    _check(to_np32(out[torch.as_tensor(tokens, device=dev)]), ref, ab, "7B shape, 2:4 weights")
+    assert torch.isfinite(out.float()).all()

@@ -20,7 +20,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "dass.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(dass_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(dass_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -42,6 +42,8 @@ def test_workspace_queries(lib):
 
 FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: every call below is rejected first
 ODD = ctypes.c_void_p(0x1004)
+FAKE2 = ctypes.c_void_p(0x10000000)  # aligned, far from FAKE
+FAKE3 = ctypes.c_void_p(0x20000000)
 
 
 def _nm(lib, W=FAKE, rows=64, cols=64, ld=64, dt=1, norms=FAKE, na=1, ga=1, alpha=1.0, n=2, m=4,
@@ -144,3 +146,47 @@ def test_input_norms_rejections(lib):
     assert _inorm(lib, wsb=64) == "DASS_ERR_WORKSPACE"
     assert lib.dass_input_norms_workspace_bytes(262144, 4096) >= 512 * 4096 * 4
     assert lib.dass_input_norms_workspace_bytes(0, 4096) == 0
+
+
+def _fwd(lib, X=FAKE, T=256, ldx=128, Wg=FAKE, Wu=FAKE, ldw=128, Wd=FAKE, ldd=192, d=128, d_int=192, dt=1, act=0,
+         out=FAKE, ldo=128, ws=FAKE, wsb=1 << 20):
+    return lib.dass_status_string(lib.dass_mlp_forward(X, T, ldx, Wg, Wu, ldw, Wd, ldd, d, d_int, dt, act, out, ldo,
+                                                       ws, wsb, None)).decode()
+
+
+def test_mlp_forward_rejections(lib):
+    assert _fwd(lib, X=None) == "DASS_ERR_NULL"
+    assert _fwd(lib, Wd=None) == "DASS_ERR_NULL"
+    assert _fwd(lib, ws=None) == "DASS_ERR_NULL"
+    assert _fwd(lib, dt=0) == "DASS_ERR_DTYPE"                  # bf16 only
+    assert _fwd(lib, act=9) == "DASS_ERR_DTYPE"
+    assert _fwd(lib, T=0) == "DASS_ERR_SHAPE"
+    assert _fwd(lib, d=96, ldx=96, ldw=96, ldo=96) == "DASS_ERR_SHAPE"     # multiples of 64
+    assert _fwd(lib, d_int=200, ldd=200) == "DASS_ERR_SHAPE"
+    assert _fwd(lib, ldd=128) == "DASS_ERR_SHAPE"
+    assert _fwd(lib, out=ODD) == "DASS_ERR_ALIGN"
+    assert _fwd(lib, ldo=132) == "DASS_ERR_ALIGN"
+    assert _fwd(lib, wsb=256 * 192 * 2 - 1) == "DASS_ERR_WORKSPACE"
+    assert lib.dass_mlp_forward_workspace_bytes(256, 128, 192, 1) == 256 * 192 * 2
+    assert lib.dass_mlp_forward_workspace_bytes(256, 128, 192, 0) == 0
+
+
+def _cmp(lib, W=FAKE, rows=64, cols=64, ld=64, dt=1, axis=1, V=FAKE2, ldv=32, M=FAKE3, ldm=8, surplus=None):
+    return lib.dass_status_string(lib.dass_compress_24(W, rows, cols, ld, dt, axis, V, ldv, M, ldm, surplus,
+                                                       None)).decode()
+
+
+def test_compress_rejections(lib):
+    assert _cmp(lib, W=None) == "DASS_ERR_NULL"
+    assert _cmp(lib, M=None) == "DASS_ERR_NULL"
+    assert _cmp(lib, dt=5) == "DASS_ERR_DTYPE"
+    assert _cmp(lib, axis=2) == "DASS_ERR_ARG"
+    assert _cmp(lib, cols=60, ld=64) == "DASS_ERR_SHAPE"                       # cols % 8
+    assert _cmp(lib, axis=0, rows=62, ldv=64, ldm=32) == "DASS_ERR_SHAPE"      # rows % 4
+    assert _cmp(lib, ldv=24) == "DASS_ERR_SHAPE"
+    assert _cmp(lib, ldm=4) == "DASS_ERR_SHAPE"
+    assert _cmp(lib, V=ODD) == "DASS_ERR_ALIGN"
+    assert _cmp(lib, axis=0, ldv=64, ldm=34) == "DASS_ERR_ALIGN"              # codes are written 4 bytes at a time
+    assert _cmp(lib, ldv=34) == "DASS_ERR_ALIGN"
+    assert _cmp(lib, surplus=ODD) == "DASS_ERR_ALIGN"
+    assert _cmp(lib, V=FAKE) == "DASS_ERR_ARG"                                 # values_out on top of W
