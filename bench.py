@@ -274,6 +274,52 @@ def main():
                  "unstructured_50pct_GBps": model_bytes / (ms_unstructured * 1e-3) / 1e9}
         del layers, tasks
 
+    # ---- pruning blocks one after the other: the pruned MLP's output (Eq. 2 + Eq. 3) over all tokens,
+    # and the 2:4 compressed form of the pruned Down-Proj and Gate-Proj ---------------------------
+    chain = None
+    if args.model_layers > 0 and Wg.dtype == torch.bfloat16 and d % 64 == 0 and I % 64 == 0 and (n_keep, m) == (2, 4):
+        pruned = [w.clone() for w in (Wg, Wu, Wd)]
+        dass.score_mask_nm(pruned[0], norms, "rows", "rows", cfg.alpha_gate_up, 2, 4, workspace=ws_gate)
+        dass.score_mask_nm(pruned[1], norms, "rows", "rows", cfg.alpha_gate_up, 2, 4, workspace=ws_gate)
+        dass.score_mask_nm(pruned[2], norms, "cols", "cols", cfg.alpha_down, 2, 4, workspace=ws_down)
+        nxt = torch.empty((T, d), dtype=Wg.dtype, device=dev)
+        ws_f = torch.empty(dass.mlp_forward_workspace_bytes(T, d, I), dtype=torch.uint8, device=dev)
+        f_ms = []
+        for it in range(4):
+            a, b = ev(), ev()
+            a.record()
+            dass.mlp_forward(X, pruned[0], pruned[1], pruned[2], cfg.act, nxt, workspace=ws_f)
+            b.record()
+            torch.cuda.synchronize()
+            if it >= 1:
+                f_ms.append(a.elapsed_time(b))
+        f_ms = statistics.median(f_ms)
+        del ws_f, nxt
+        cmp_us = {}
+        for name, w, axis in (("down_cols", pruned[2], "cols"), ("gate_rows", pruned[0], "rows")):
+            rows, cols = w.shape
+            vals = torch.empty((rows // 2, cols) if axis == "rows" else (rows, cols // 2), dtype=w.dtype, device=dev)
+            meta = torch.empty((rows // 4, cols // 2) if axis == "rows" else (rows, cols // 8), dtype=torch.uint8,
+                               device=dev)
+            copies = [w.clone() for _ in range(n_copies)]   # rotate through > 256 MB, as for stage 2
+            ts = []
+            for it in range(12):
+                a, b = ev(), ev()
+                a.record()
+                dass.compress_24(copies[it % n_copies], axis, vals, meta)
+                b.record()
+                torch.cuda.synchronize()
+                if it >= 4:
+                    ts.append(a.elapsed_time(b))
+            cmp_us[name] = statistics.median(ts) * 1e3
+            del copies, vals, meta
+        cmp_bytes = Wd.numel() * (esz + esz / 2.0 + 0.125)   # read W, write half of it and 1 bit per weight
+        chain = {"mlp_forward_ms": f_ms, "mlp_forward_TFLOPs": 6.0 * T * d * I / (f_ms * 1e-3) / 1e12,
+                 "mlp_forward_frac_of_mfma_peak": 6.0 * T * d * I / (f_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                 "compress_24_us": cmp_us, "compress_24_bytes": cmp_bytes,
+                 "compress_24_GBps": {k: cmp_bytes / (v * 1e-6) / 1e9 for k, v in cmp_us.items()}}
+        del pruned
+
     out = {
         "metric": "calib tokens/s (fused GLU-norm, %MFMA peak) + N:M mask GB/s, LLaMA2-7B MLP",
         "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -300,6 +346,8 @@ def main():
     out["input_norms_eq1"] = input_norms
     if model is not None:
         out["stage2_whole_model"] = model
+    if chain is not None:
+        out["layer_chaining"] = chain
     if not args.no_cpu_baseline:
         n_sample = min(T, 8192)   # about 14 s of the oracle on 16 host threads
         out["cpu_baseline"] = cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X[:n_sample],

@@ -91,8 +91,10 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
         }
     }
     int surplus = 0;
+    uint32_t outv[kCmpUnits][4], outb[kCmpUnits];
 #pragma unroll
     for (int k = 0; k < kCmpUnits; ++k) {
+        outv[k][0] = outv[k][1] = outv[k][2] = outv[k][3] = outb[k] = 0;
         if (unit[k] >= units)
             continue;
         uint32_t kept[4], byte = 0;
@@ -114,16 +116,48 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
             kept[2 * g + 1] = p1 == 1 ? b[1] : p1 == 2 ? b[2] : b[3];    // p1 >= 1
             byte |= code << (4 * g);
         }
+        outv[k][0] = DT == DASS_BF16 ? kept[0] | kept[1] << 16 : kept[0];
+        outv[k][1] = DT == DASS_BF16 ? kept[2] | kept[3] << 16 : kept[1];
+        outv[k][2] = kept[2];
+        outv[k][3] = kept[3];
+        outb[k] = byte;
+    }
+    // Stores.  Neighbouring lanes hold neighbouring units (a thread's unit index has the parity
+    // of its lane), so two lanes' bf16 values make one 16-byte store and four lanes' codes one
+    // 32-bit store where the row's alignment allows; the ragged end of a row and unaligned rows
+    // store piecewise.  Every lane takes part in the exchanges.
+    const int lane = threadIdx.x & 63;
+    const bool wide_v = ((reinterpret_cast<uintptr_t>(V)) & 15u) == 0;
+    const bool wide_m = ((reinterpret_cast<uintptr_t>(M)) & 3u) == 0;
+#pragma unroll
+    for (int k = 0; k < kCmpUnits; ++k) {
+        const bool have = unit[k] < units;
         if constexpr (DT == DASS_BF16) {
-            uint2 o;
-            o.x = kept[0] | kept[1] << 16;
-            o.y = kept[2] | kept[3] << 16;
-            *reinterpret_cast<uint2 *>(V + unit[k] * 8) = o;
-        } else {
-            u32x4 o = {kept[0], kept[1], kept[2], kept[3]};
+            const uint32_t nx = __shfl_down(outv[k][0], 1, 64), ny = __shfl_down(outv[k][1], 1, 64);
+            const bool pair = wide_v && unit[k] + 1 < units;   // uniform over a lane pair
+            if (have && pair && (lane & 1) == 0) {
+                u32x4 o = {outv[k][0], outv[k][1], nx, ny};
+                *reinterpret_cast<u32x4 *>(V + unit[k] * 8) = o;
+            } else if (have && !(wide_v && (lane & 1) && unit[k] < units)) {
+                uint2 o;
+                o.x = outv[k][0];
+                o.y = outv[k][1];
+                *reinterpret_cast<uint2 *>(V + unit[k] * 8) = o;
+            }
+        } else if (have) {
+            u32x4 o = {outv[k][0], outv[k][1], outv[k][2], outv[k][3]};
             *reinterpret_cast<u32x4 *>(V + unit[k] * 16) = o;
         }
-        M[unit[k]] = (uint8_t)byte;
+        const uint32_t b1 = __shfl_down(outb[k], 1, 64), b2 = __shfl_down(outb[k], 2, 64),
+                       b3 = __shfl_down(outb[k], 3, 64);
+        const int64_t quad = unit[k] & ~(int64_t)3;   // first unit of this lane's group of four
+        const bool whole = wide_m && quad + 3 < units;   // uniform over the four lanes
+        if (have && whole) {
+            if ((lane & 3) == 0)
+                *reinterpret_cast<uint32_t *>(M + unit[k]) = outb[k] | b1 << 8 | b2 << 16 | b3 << 24;
+        } else if (have) {
+            M[unit[k]] = (uint8_t)outb[k];
+        }
     }
     add_surplus(surplus_out, surplus);
 }
