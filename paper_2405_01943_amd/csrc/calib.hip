@@ -627,9 +627,10 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     uint32_t a_off[A_WL], b_off[B_WL];
 #pragma unroll
     for (int p = 0; p < A_WL; ++p) {
+        // rows past T are not clamped: they lie beyond the end of the buffer and read as 0, which
+        // the epilogues rely on (act(0) * 0 adds nothing to a norm; stores are bounded by T)
         const int r = (wave * A_WL + p) * 8 + wl_row;
-        const int64_t rr = r < rows_x ? r : rows_x - 1;
-        a_off[p] = (uint32_t)(rr * ldx * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
+        a_off[p] = (uint32_t)((int64_t)r * ldx * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
     }
 #pragma unroll
     for (int p = 0; p < B_WL; ++p) {
@@ -831,9 +832,13 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 
     if constexpr (EPI == kEpiNorms) {
         // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens (tokens are the
-        // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  One code path for
-        // whole and ragged tiles: a second, maskless copy of this loop nest measured slower overall.
-        const int valid = t0 + BM <= T ? BM : (int)(T - t0);   // tokens of this tile that exist
+        // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  Tokens past T
+        // were read as zeros, so their y is 0 and no test is needed.  The lane's neuron index is
+        // derived here from the lane number afresh: nothing per-lane has to survive the main loop
+        // for it (the loop uses every register, and a spill would give the kernel a scratch segment).
+        uint32_t lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(lane_e));
+        const int fr_e = lane_e & 31, fc_e = lane_e >> 5;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             float part = 0.0f;
@@ -842,13 +847,12 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
-                    const int t = wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
-                    part += t < valid ? y * y : 0.0f;
+                    part = fmaf(y, y, part);
                 }
             }
             part += __shfl_xor(part, 32, 64);
-            const int64_t n = n0 + wn * TN + j * 32 + fr;
-            if (fc == 0 && n < d_int)
+            const int64_t n = n0 + wn * TN + j * 32 + fr_e;
+            if (fc_e == 0 && n < d_int)
                 atomicAdd(sumsq + n, part);
         }
     } else {
