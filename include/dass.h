@@ -198,7 +198,10 @@ dass_status dass_input_norms(const void *X, int64_t T, int64_t ldx, int64_t d, d
  * converts a sparsity ratio s to n_prune = floor(s * line length).
  *
  *   workspace  device scratch of at least dass_unstructured_workspace_bytes()
- *              bytes, 16-byte aligned (holds f and the per-line selection state).
+ *              bytes, 16-byte aligned (holds f and the per-line selection state;
+ *              for column lines of more than 16384 bf16 / 8192 f32 weights also a
+ *              transposed copy of W, rows * cols elements, on which such lines
+ *              are selected).
  */
 size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, dass_dtype dt,
                                          dass_axis norm_axis, dass_axis group_axis);

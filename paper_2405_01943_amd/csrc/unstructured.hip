@@ -1040,15 +1040,139 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     }
 }
 
+// ---------------------------------------------------------------- transpose --
+// Column lines too long for one workgroup's registers (more than 16384 rows of bf16) are
+// selected on a transposed copy, where they are row lines: dst[c, r] = src[r, c], 64 x 64
+// element tiles through LDS, 16-byte accesses on both sides (8 consecutive lanes cover 128
+// contiguous bytes of a row).  The LDS row stride in dwords is odd, so that the column gather of
+// the second phase spreads over the banks.
+template <int DT>
+__global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__ srcv, int64_t rows, int64_t cols,
+                                                        int64_t ld, void *__restrict__ dstv, int64_t ldd,
+                                                        uint32_t tiles_c)
+{
+    constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
+    constexpr int EB = DT == DASS_BF16 ? 2 : 4;
+    constexpr int TS = 64, VPR = TS / EPV;
+    constexpr int ROW_DW = TS * EB / 4 + 1;
+    __shared__ uint32_t tile[TS * ROW_DW];
+    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * TS, c0 = (int64_t)(blockIdx.x % tiles_c) * TS;
+    const char *src = static_cast<const char *>(srcv);
+    char *dst = static_cast<char *>(dstv);
+    for (int v = threadIdx.x; v < TS * VPR; v += 256) {
+        const int r = v / VPR, cv = v % VPR;
+        if (r0 + r < rows && c0 + cv * EPV < cols) {   // rows and cols are multiples of EPV: whole vectors
+            const u32x4 x = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(src + ((r0 + r) * ld + c0 + cv * EPV) * EB));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                tile[r * ROW_DW + cv * 4 + i] = x[i];
+        }
+    }
+    __syncthreads();
+    for (int v = threadIdx.x; v < TS * VPR; v += 256) {
+        const int rg = v % VPR, c = v / VPR;   // destination row c0 + c, its vector of source rows rg * EPV ..
+        if (c0 + c < cols && r0 + rg * EPV < rows) {
+            u32x4 x;
+            if constexpr (DT == DASS_BF16) {
+                const uint16_t *t16 = reinterpret_cast<const uint16_t *>(tile);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    x[i] = (uint32_t)t16[(rg * EPV + 2 * i) * ROW_DW * 2 + c] |
+                           (uint32_t)t16[(rg * EPV + 2 * i + 1) * ROW_DW * 2 + c] << 16;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    x[i] = tile[(rg * EPV + i) * ROW_DW + c];
+            }
+            __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(dst + ((c0 + c) * ldd + r0 + rg * EPV) * EB));
+        }
+    }
+}
+
+// Launch plan of the resident kernel for a matrix, or fits = false.
+struct ResidentPlan {
+    bool fits;
+    int vpl_log2, lpb;
+    int64_t grid;
+    size_t smem;
+};
+static ResidentPlan plan_resident(int64_t rows, int64_t cols, int64_t ld, int dt, bool gate, bool along)
+{
+    ResidentPlan p{false, 0, kLrLines, 0, 0};
+    const int epv = vec_elems(dt);
+    const int64_t len = gate ? rows : cols;
+    if (len > 0xFFFF)
+        return p;
+    if (gate) {   // a thread holds 8 / epv vectors of every 1024th row
+        p.fits = (rows + kLrThreads - 1) / kLrThreads * (8 / epv) <= kLrVecs;
+        p.grid = (cols / 8 + 63) / 64 * 64;
+    } else {      // a thread holds 2^vpl_log2 vectors of each of its workgroup's lines
+        const int64_t vpl = (cols / epv + kLrThreads - 1) / kLrThreads;
+        while ((1 << p.vpl_log2) < vpl && p.vpl_log2 < 5)
+            ++p.vpl_log2;
+        p.fits = (1 << p.vpl_log2) <= kLrVecs;
+        if (p.fits && kLrVecs >> p.vpl_log2 < p.lpb)
+            p.lpb = kLrVecs >> p.vpl_log2;
+        p.grid = (rows + p.lpb - 1) / p.lpb;
+    }
+    p.smem = (size_t)p.lpb * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 + 256 + kLrLines * 4 +
+             kLrLines * kLrTies * 8 + (along ? (size_t)len : (size_t)kLrLines) * sizeof(float);
+    p.fits = p.fits && p.grid <= 0x7fffffffLL && p.smem <= 160 * 1024 &&
+             rows * ld * elem_bytes(dt) < (1LL << 32);
+    return p;
+}
+
+static dass_status launch_resident(const char *fn, const ResidentPlan &p, void *W, int64_t rows, int64_t cols,
+                                   int64_t ld, int dt, const float *norms, bool gate, bool along, int fmode,
+                                   uint32_t n_keep, uint8_t *mask_out, hipStream_t stream)
+{
+    using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int, int);
+    k_t k;
+    if (dt == DASS_BF16)
+        k = gate ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
+                          : unstructured_resident_kernel<DASS_BF16, kLrGate, false>)
+                 : (along ? unstructured_resident_kernel<DASS_BF16, kLrDown, true>
+                          : unstructured_resident_kernel<DASS_BF16, kLrDown, false>);
+    else
+        k = gate ? (along ? unstructured_resident_kernel<DASS_F32, kLrGate, true>
+                          : unstructured_resident_kernel<DASS_F32, kLrGate, false>)
+                 : (along ? unstructured_resident_kernel<DASS_F32, kLrDown, true>
+                          : unstructured_resident_kernel<DASS_F32, kLrDown, false>);
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)p.smem) != hipSuccess)
+        return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, p.smem);
+    hipLaunchKernelGGL(k, dim3((unsigned)p.grid), dim3(kLrThreads), p.smem, stream, W, rows, cols, ld, norms, fmode,
+                       n_keep, mask_out, p.vpl_log2, p.lpb);
+    return check_launch("unstructured kernel");
+}
+
+// Column lines that do not fit the resident kernel but would as row lines of the transposed
+// matrix [cols, rows]: the plan for that matrix (leading dimension rows), or fits = false.
+static ResidentPlan plan_transposed(int64_t rows, int64_t cols, int dt, bool along)
+{
+    if (rows % vec_elems(dt) != 0)
+        return ResidentPlan{false, 0, 0, 0, 0};
+    return plan_resident(cols, rows, rows, dt, false, along);
+}
+
 }  // namespace dass
 
 extern "C" size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, dass_dtype dt,
                                                     dass_axis norm_axis, dass_axis group_axis)
 {
-    (void)dt;
-    (void)group_axis;
+    using namespace dass;
     const int64_t n = norm_axis == DASS_AXIS_ROWS ? rows : cols;
-    return n > 0 ? dass::round_up((size_t)n * sizeof(float), 256) : 0;
+    if (n <= 0 || rows <= 0 || cols <= 0)
+        return 0;
+    size_t bytes = round_up((size_t)n * sizeof(float), 256);
+    // long column lines are selected on a transposed copy of the matrix
+    if (valid_dtype(dt) && group_axis == DASS_AXIS_ROWS && cols % 8 == 0) {
+        const bool along = norm_axis == group_axis;
+        if (!plan_resident(rows, cols, cols, dt, true, along).fits && plan_transposed(rows, cols, dt, along).fits)
+            bytes += (size_t)rows * (size_t)cols * elem_bytes(dt);
+    }
+    return bytes;
 }
 
 extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, int64_t ld,
@@ -1087,45 +1211,30 @@ extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64
         const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
         const bool along = norm_axis == group_axis;
         const bool gate = group_axis == DASS_AXIS_ROWS;
-        const int epv = vec_elems(dt);
-        bool fits;
-        int vpl_log2 = 0, lpb = kLrLines;
-        int64_t grid;
-        if (gate) {   // a thread holds 8 / epv vectors of every 1024th row
-            fits = (rows + kLrThreads - 1) / kLrThreads * (8 / epv) <= kLrVecs;
-            grid = (cols / 8 + 63) / 64 * 64;
-        } else {      // a thread holds 2^vpl_log2 vectors of each of its workgroup's lines
-            const int64_t vpl = (cols / epv + kLrThreads - 1) / kLrThreads;
-            while ((1 << vpl_log2) < vpl && vpl_log2 < 5)
-                ++vpl_log2;
-            fits = (1 << vpl_log2) <= kLrVecs;
-            if (fits && kLrVecs >> vpl_log2 < lpb)
-                lpb = kLrVecs >> vpl_log2;
-            grid = (rows + lpb - 1) / lpb;
-        }
-        const size_t smem = (size_t)lpb * kLrBins * 4 + kLrLines * sizeof(LrState) + 16 + 256 +
-                            kLrLines * 4 + kLrLines * kLrTies * 8 +
-                            (along ? (size_t)len : (size_t)kLrLines) * sizeof(float);
-        if (fits && grid <= 0x7fffffffLL && smem <= 160 * 1024 && rows * ld * (bf16 ? 2 : 4) < (1LL << 32)) {
-            using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int,
-                                 int);
-            k_t k;
-            if (bf16)
-                k = gate ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
-                                  : unstructured_resident_kernel<DASS_BF16, kLrGate, false>)
-                         : (along ? unstructured_resident_kernel<DASS_BF16, kLrDown, true>
-                                  : unstructured_resident_kernel<DASS_BF16, kLrDown, false>);
-            else
-                k = gate ? (along ? unstructured_resident_kernel<DASS_F32, kLrGate, true>
-                                  : unstructured_resident_kernel<DASS_F32, kLrGate, false>)
-                         : (along ? unstructured_resident_kernel<DASS_F32, kLrDown, true>
-                                  : unstructured_resident_kernel<DASS_F32, kLrDown, false>);
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)smem) != hipSuccess)
-                return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, smem);
-            hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(kLrThreads), smem, stream, W, rows, cols, ld, norms,
-                               fmode, n_keep, mask_out, vpl_log2, lpb);
-            return check_launch("unstructured kernel");
+        const ResidentPlan p = plan_resident(rows, cols, ld, dt, gate, along);
+        if (p.fits)
+            return launch_resident(fn, p, W, rows, cols, ld, dt, norms, gate, along, fmode, n_keep, mask_out, stream);
+        // Longer column lines: transpose into the workspace, select there along the rows, transpose
+        // back.  (No mask in this form: its bits would come out transposed.)
+        const ResidentPlan pt = gate && !mask_out ? plan_transposed(rows, cols, dt, along) : ResidentPlan{false, 0, 0, 0, 0};
+        const size_t f_bytes = round_up((size_t)(norm_axis == DASS_AXIS_ROWS ? rows : cols) * sizeof(float), 256);
+        if (pt.fits && workspace_bytes >= f_bytes + (size_t)rows * cols * elem_bytes(dt)) {
+            void *Wt = static_cast<char *>(workspace) + f_bytes;
+            const int64_t tiles_r = (rows + 63) / 64, tiles_c = (cols + 63) / 64;
+            if (tiles_r * tiles_c > 0x7fffffffLL)
+                return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch", fn);
+            auto tk = bf16 ? transpose_kernel<DASS_BF16> : transpose_kernel<DASS_F32>;
+            hipLaunchKernelGGL(tk, dim3((unsigned)(tiles_r * tiles_c)), dim3(256), 0, stream, (const void *)W, rows,
+                               cols, ld, Wt, rows, (uint32_t)tiles_c);
+            s = check_launch("transpose kernel");
+            if (s != DASS_OK)
+                return s;
+            s = launch_resident(fn, pt, Wt, cols, rows, rows, dt, norms, false, along, fmode, n_keep, nullptr, stream);
+            if (s != DASS_OK)
+                return s;
+            hipLaunchKernelGGL(tk, dim3((unsigned)(tiles_r * tiles_c)), dim3(256), 0, stream, (const void *)Wt, cols,
+                               rows, rows, W, ld, (uint32_t)tiles_r);
+            return check_launch("transpose kernel");
         }
     }
 

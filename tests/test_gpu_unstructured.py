@@ -180,6 +180,42 @@ def test_unstructured_long_row_lines(gpu_device, dtype, cols):
         assert np.array_equal(mask.cpu().numpy(), want_mask)
 
 
+@pytest.mark.parametrize("dtype,rows,cols,pad", [(torch.bfloat16, 28672, 72, 0), (torch.bfloat16, 24576, 136, 8),
+                                                 (torch.bfloat16, 16392, 8, 0), (torch.bfloat16, 40000, 64, 0),
+                                                 (torch.float32, 9000, 24, 4), (torch.float32, 20000, 72, 0)])
+def test_unstructured_long_column_lines(gpu_device, dtype, rows, cols, pad):
+    """Column lines longer than a workgroup's registers hold (LLaMA2-70B and Gemma-7B Gate-Proj
+    columns among them): selected on a transposed copy in the workspace.  With a mask requested
+    the call takes the multi-pass kernels instead; both must equal the oracle."""
+    g = torch.Generator(device="cpu").manual_seed(rows + cols)
+    W0 = (torch.randn((rows, cols), generator=g) * 0.02).to(dtype)
+    W0[torch.rand((rows, cols), generator=g) < 0.05] = 0.0
+    cases = ((("rows", "rows"), 0.5, rows // 2), (("rows", "rows"), 1.0, rows // 3 + 1), (("cols", "rows"), 0.5, rows // 2),
+             (("rows", "rows"), 0.0, rows - 5))
+    for k, (axes, alpha, n_prune) in enumerate(cases):
+        nrm = synth.make_norms(rows if axes[0] == "rows" else cols, "cpu", k).to(gpu_device)
+        W = W0.to(gpu_device)
+        if pad:
+            W = padded(W, pad)
+        want, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), axes[0], axes[1], alpha, n_prune,
+                                                   want_mask=True)
+        need = dass.unstructured_workspace_bytes(rows, cols, dtype, axes[0], axes[1])
+        if rows <= 32768:   # room for the transposed copy (longer lines: their factors no longer fit in LDS)
+            assert need >= rows * cols * W.element_size()
+        dass.score_mask_unstructured(W, nrm, axes[0], axes[1], alpha, n_prune)
+        torch.cuda.synchronize()
+        assert bits_equal(W, want), f"{axes} alpha={alpha}: {first_mismatch(W, want)}"
+        if pad:
+            assert torch.all(W._base[:, cols:] == 7.0)
+        if k == 0:   # the same case with a mask
+            W2 = W0.to(gpu_device)
+            mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+            dass.score_mask_unstructured(W2, nrm, axes[0], axes[1], alpha, n_prune, mask_out=mask)
+            torch.cuda.synchronize()
+            assert bits_equal(W2, want), first_mismatch(W2, want)
+            assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
