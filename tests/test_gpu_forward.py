@@ -1,10 +1,14 @@
 """GPU parity: dass_mlp_forward (Eq. 2 then Eq. 3, bf16) against the float64 oracle.
 
-Tolerance, derived from the arithmetic: y is rounded to bf16 once (relative error <= 2^-9 per
-term of the Eq. 3 sum), the output once (2^-9 of its value), sums accumulate in f32
-(K * 2^-24 <= 6.6e-4 of the terms' absolute sum at the worst, far less in practice).  With
-A = sum_i |y_i Wdown[j, i]| from the oracle:  |gpu - oracle| <= 2^-8 A + 2^-8 |oracle|,
-i.e. twice the two rounding bounds.
+Tolerance, derived from the arithmetic.  bf16 keeps 8 significant bits: rounding to nearest has
+relative error at most u = 2^-8.  With A = sum_i |y_i Wdown[j, i]| from the oracle:
+  - y is rounded to bf16 once: every term of the Eq. 3 sum moves by at most u of itself, the sum
+    by at most u A;
+  - the f32 evaluation of y and the f32 accumulation of the sum add at most (eps + K 2^-24) A,
+    K = d_int <= 28672, i.e. less than 0.5 u A even by the worst-case linear bound;
+  - the output is rounded to bf16 once: at most u of its value.
+Hence |gpu - oracle| <= u |oracle| + 1.5 u A (second-order terms fall inside the slack of the
+last factor).
 """
 import numpy as np
 import pytest
@@ -21,7 +25,7 @@ pytestmark = pytest.mark.gpu
 
 def _check(out, ref, ab, what):
     out = np.asarray(out, dtype=np.float64)
-    tol = 2.0 ** -8 * ab + 2.0 ** -8 * np.abs(ref) + 1e-30
+    tol = 2.0 ** -8 * (np.abs(ref) + 1.5 * ab) + 1e-30
     err = np.abs(out - ref)
     worst = float(np.max(err / tol))
     assert worst <= 1.0, f"{what}: worst error / tolerance = {worst:.3f}"
