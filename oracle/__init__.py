@@ -58,6 +58,8 @@ def _load():
         lib.oracle_mlp_forward.argtypes = [vp, i64, i64, vp, vp, i64, vp, i64, i64, i64, ci, vp, i64, vp, vp]
         lib.oracle_compress_24.restype = i64
         lib.oracle_compress_24.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64]
+        lib.oracle_down_sparse24.restype = None
+        lib.oracle_down_sparse24.argtypes = [vp, i64, i64, vp, i64, vp, i64, i64, i64, vp, i64, vp, vp]
         lib.oracle_num_threads.restype = ci
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -238,3 +240,26 @@ def compress_24(W, group_axis: str):
     if rc < 0:
         raise ValueError("oracle_compress_24 rejected the shape")
     return values, meta, int(rc)
+
+
+def down_sparse24(Y, values, meta, tokens=None, want_abs: bool = False):
+    """Eq. 3 from the 2:4 compressed Down-Proj (groups along the columns): out = Y W^T in float64."""
+    Y, values = _f32_2d(Y, "Y"), _f32_2d(values, "values")
+    meta = np.asarray(meta)
+    T, d_int = Y.shape
+    d = values.shape[0]
+    if meta.dtype != np.uint8 or meta.ndim != 2 or not meta.flags.c_contiguous:
+        raise TypeError("meta: need a contiguous 2-D uint8 array")
+    if d_int % 8 != 0 or values.shape != (d, d_int // 2) or meta.shape != (d, d_int // 8):
+        raise ValueError("shape mismatch between Y, values and meta")
+    if tokens is not None:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+        if tokens.size and (tokens.min() < 0 or tokens.max() >= T):
+            raise ValueError("token index out of range")
+    n = T if tokens is None else tokens.size
+    out = np.empty((n, d), dtype=np.float64)
+    absout = np.empty((n, d), dtype=np.float64) if want_abs else None
+    _load().oracle_down_sparse24(_ptr(Y), T, _ld(Y), _ptr(values), _ld(values), _ptr(meta), meta.shape[1], d, d_int,
+                                 None if tokens is None else _ptr(tokens), n, _ptr(out),
+                                 None if absout is None else _ptr(absout))
+    return (out, absout) if want_abs else out

@@ -23,6 +23,7 @@
  *     block (with pruned weights: the next block's calibration input).
  *   - oracle_compress_24          : the 2:4 pattern of Sec. 2.2 "N:M sparsity" stored as kept
  *     values plus 2-bit positions (the form sparse matrix units consume).
+ *   - oracle_down_sparse24        : Eq. 3 evaluated from that stored form.
  *
  * Inputs are float arrays holding exactly the values the GPU sees (a bf16
  * value widens to float without rounding); all arithmetic is double.  The
@@ -39,7 +40,7 @@
  * values, chunk additivity; sums of squares of integers and a hand-worked Wanda selection for
  * the input norms; one-hot closed forms, a library matrix product and the identity with
  * oracle_sumsq for the MLP output; a hand-worked example and the round trip for the compressed
- * form).  No function here is "parity unpinned".
+ * form; a library product with the decoded matrix and a hand-worked row for Eq. 3 from it).  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -384,6 +385,41 @@ int64_t oracle_compress_24(const float *W, int64_t rows, int64_t cols, int64_t l
         }
     }
     return surplus;
+}
+
+/*
+ * Eq. 3 with Down-Proj given in the 2:4 compressed form above (groups along the columns):
+ *   out[t, j] = sum over groups g and stored values s of  values[j, 2 g + s] * Y[t, 4 g + p_s],
+ * p_0 = code & 3, p_1 = code >> 2, code = nibble (g & 1) of meta[j, g / 2] -- i.e. Y times the
+ * transpose of the matrix the compressed form stands for, summed in double, g ascending.
+ *   Y      : [T, d_int] row-major, row stride ldy
+ *   values : [d, d_int / 2], row stride ldv;  meta : [d, d_int / 8] bytes, row stride ldm
+ *   tokens : n_sel row indices into Y, or NULL for all T rows
+ *   out, absout : [n_sel, d] doubles (absout may be NULL): the sum and the sum of magnitudes
+ */
+void oracle_down_sparse24(const float *Y, int64_t T, int64_t ldy, const float *values, int64_t ldv,
+                          const uint8_t *meta, int64_t ldm, int64_t d, int64_t d_int,
+                          const int64_t *tokens, int64_t n_sel, double *out, double *absout)
+{
+    const int64_t n = tokens ? n_sel : T;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < n; ++k) {
+        const float *y = Y + (tokens ? tokens[k] : k) * ldy;
+        for (int64_t j = 0; j < d; ++j) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t g = 0; g < d_int / 4; ++g) {
+                const int code = (meta[j * ldm + (g >> 1)] >> (4 * (g & 1))) & 15;
+                const double t0 = (double)values[j * ldv + 2 * g] * (double)y[4 * g + (code & 3)];
+                const double t1 = (double)values[j * ldv + 2 * g + 1] * (double)y[4 * g + (code >> 2)];
+                acc += t0;
+                acc += t1;
+                aacc += fabs(t0) + fabs(t1);
+            }
+            out[k * d + j] = acc;
+            if (absout)
+                absout[k * d + j] = aacc;
+        }
+    }
 }
 
 /* Number of OpenMP threads the loops above will use (for the baseline report). */

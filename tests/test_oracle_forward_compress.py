@@ -157,3 +157,41 @@ def test_dense_groups_are_counted_and_bad_shapes_rejected():
         oracle.compress_24(np.ones((4, 12), dtype=np.float32), "cols")   # cols % 8
     with pytest.raises(ValueError):
         oracle.compress_24(np.ones((6, 8), dtype=np.float32), "rows")    # rows % 4
+
+
+# ------------------------------------------------- Eq. 3 from the 2:4 form --
+def test_down_sparse24_hand_worked_row():
+    """One output feature, two groups: values (2, -3 | 0.5, 4) at positions (1, 3 | 0, 2):
+    out = 2 y1 - 3 y3 + 0.5 y4 + 4 y6, written out by hand for y = 1..8."""
+    values = np.array([[2.0, -3.0, 0.5, 4.0]], dtype=np.float32)
+    meta = np.array([[(1 | 3 << 2) | (0 | 2 << 2) << 4]], dtype=np.uint8)
+    Y = np.arange(1, 9, dtype=np.float32)[None, :]
+    out, ab = oracle.down_sparse24(Y, values, meta, want_abs=True)
+    assert out.tolist() == [[2 * 2 - 3 * 4 + 0.5 * 5 + 4 * 7]]        # y1 = 2, y3 = 4, y4 = 5, y6 = 7
+    assert ab.tolist() == [[4 + 12 + 2.5 + 28]]
+
+
+def test_down_sparse24_equals_a_library_product_with_the_decoded_matrix():
+    rng = np.random.default_rng(8)
+    d, d_int, T = 12, 64, 9
+    W = rng.standard_normal((d, d_int)).astype(np.float32)
+    for row in W:
+        for g in range(d_int // 4):
+            row[4 * g + rng.choice(4, size=2, replace=False)] = 0.0
+    W[rng.random(W.shape) < 0.1] = 0.0
+    values, meta, surplus = oracle.compress_24(W, "cols")
+    assert surplus == 0 and np.array_equal(_decompress(values, meta, "cols", W.shape), W)
+    Y = rng.standard_normal((T, d_int)).astype(np.float32)
+    want = Y.astype(np.float64) @ W.astype(np.float64).T
+    got = oracle.down_sparse24(Y, values, meta)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-14)
+    tok = np.array([8, 0, 3])
+    assert np.array_equal(oracle.down_sparse24(Y, values, meta, tokens=tok), got[tok])
+    # and it continues Eq. 2: with y from the dense oracle the two routes to the block output agree
+    X = rng.standard_normal((T, d)).astype(np.float32)
+    Wg = rng.standard_normal((d_int, d)).astype(np.float32)
+    Wu = rng.standard_normal((d_int, d)).astype(np.float32)
+    full = oracle.mlp_forward(X, Wg, Wu, W, "silu")
+    g64 = X.astype(np.float64) @ Wg.astype(np.float64).T
+    y = (g64 / (1.0 + np.exp(-g64)) * (X.astype(np.float64) @ Wu.astype(np.float64).T)).astype(np.float32)
+    np.testing.assert_allclose(oracle.down_sparse24(y, values, meta), full, rtol=1e-5, atol=1e-6)
