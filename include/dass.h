@@ -276,6 +276,26 @@ dass_status dass_compress_24(const void *W, int64_t rows, int64_t cols, int64_t 
                              uint8_t *meta_out, int64_t ldm, long long *surplus_out,
                              void *hip_stream);
 
+/*
+ * Eq. 3 (Sec. 2.2) from the compressed Down-Proj: out = Y Wdown^T, Wdown given
+ * as dass_compress_24(..., group_axis = DASS_AXIS_COLS) wrote it, evaluated
+ * on the sparse matrix cores - the hardware use of 2:4 sparsity that Sec. 2.2
+ * names.
+ *
+ *   Y       [T, d_int] row stride ldy (the y of Eq. 2), device, read only
+ *   values  [d, d_int / 2] row stride ldv;  meta [d, d_int / 8] bytes, row
+ *           stride ldm: the compressed form, device, read only
+ *   out     [T, d] row stride ldo, device, overwritten
+ * dt: DASS_BF16 only.  Products accumulate in f32, out is rounded to bf16 once.
+ * d_int a multiple of 64, d of 8 (DASS_ERR_SHAPE); Y, values, out 16-byte
+ * aligned with leading dimensions multiples of 8, meta 4-byte aligned with
+ * ldm a multiple of 4 (DASS_ERR_ALIGN).  One launch on hip_stream.
+ */
+dass_status dass_down_proj_sparse24(const void *Y, int64_t T, int64_t ldy, const void *values,
+                                    int64_t ldv, const uint8_t *meta, int64_t ldm, int64_t d,
+                                    int64_t d_int, dass_dtype dt, void *out, int64_t ldo,
+                                    void *hip_stream);
+
 const char *dass_status_string(dass_status s);
 /* Detail of the calling thread's most recent failed call ("" if none). */
 const char *dass_last_error_string(void);

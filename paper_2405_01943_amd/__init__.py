@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     ACT, AXIS, DTYPE, DassError,
     calib_norms, calib_workspace_bytes,
     input_norms, input_norms_workspace_bytes,
-    mlp_forward, mlp_forward_workspace_bytes, compress_24,
+    mlp_forward, mlp_forward_workspace_bytes, compress_24, down_proj_sparse24,
     score_mask_nm, nm_workspace_bytes,
     score_mask_nm_batched, nm_batched_workspace_bytes,
     score_mask_unstructured, unstructured_workspace_bytes,

@@ -26,7 +26,7 @@ EXPORTS = (
     "dass_nm_batched_workspace_bytes", "dass_score_mask_nm_batched",
     "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
     "dass_input_norms_workspace_bytes", "dass_input_norms",
-    "dass_mlp_forward_workspace_bytes", "dass_mlp_forward", "dass_compress_24",
+    "dass_mlp_forward_workspace_bytes", "dass_mlp_forward", "dass_compress_24", "dass_down_proj_sparse24",
     "dass_status_string", "dass_last_error_string", "dass_version",
 )
 
@@ -95,6 +95,8 @@ def load_library() -> ctypes.CDLL:
                                      vp, sz, vp]
     lib.dass_compress_24.restype = ci
     lib.dass_compress_24.argtypes = [vp, i64, i64, i64, ci, ci, vp, i64, vp, i64, vp, vp]
+    lib.dass_down_proj_sparse24.restype = ci
+    lib.dass_down_proj_sparse24.argtypes = [vp, i64, i64, vp, i64, vp, i64, i64, i64, ci, vp, i64, vp]
     lib.dass_status_string.restype = ctypes.c_char_p
     lib.dass_status_string.argtypes = [ci]
     lib.dass_last_error_string.restype = ctypes.c_char_p
@@ -332,4 +334,20 @@ def compress_24(W: torch.Tensor, group_axis: str, values_out: torch.Tensor, meta
         raise TypeError("surplus_out: need one int64")
     _check(lib.dass_compress_24(_ptr(W), rows, cols, ld, DTYPE[W.dtype], AXIS[group_axis], _ptr(values_out), ldv,
                                 _ptr(meta_out), ldm, _ptr(surplus_out), _stream(stream)))
+
+
+def down_proj_sparse24(Y: torch.Tensor, values: torch.Tensor, meta: torch.Tensor, out: torch.Tensor,
+                       stream=None) -> None:
+    """dass_down_proj_sparse24: out = Y Wdown^T from the 2:4 compressed Down-Proj (sparse MFMA)."""
+    lib = load_library()
+    T, d_int, ldy = _matrix(Y, "Y")
+    d, half, ldv = _matrix(values, "values")
+    To, do, ldo = _matrix(out, "out")
+    if half * 2 != d_int or (To, do) != (T, d) or values.dtype != Y.dtype or out.dtype != Y.dtype:
+        raise ValueError("need values [d, d_int / 2] and out [T, d] in Y's dtype")
+    if meta.dtype != torch.uint8 or meta.dim() != 2 or tuple(meta.shape) != (d, d_int // 8) or meta.stride(1) != 1:
+        raise TypeError("meta: need uint8 [d, d_int / 8]")
+    ldm = meta.stride(0) if meta.shape[0] > 1 else max(meta.stride(0), meta.shape[1])
+    _check(lib.dass_down_proj_sparse24(_ptr(Y), T, ldy, _ptr(values), ldv, _ptr(meta), ldm, d, d_int,
+                                       DTYPE[Y.dtype], _ptr(out), ldo, _stream(stream)))
 

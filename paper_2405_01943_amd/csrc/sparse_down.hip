@@ -1,0 +1,273 @@
+// Eq. 3 (Sec. 2.2) from the 2:4 compressed Down-Proj: out = y Wdown^T on the sparse matrix cores
+// (v_smfmac_f32_32x32x32_bf16), the hardware use of N:M sparsity that Sec. 2.2 points to.
+//
+// The sparse operand of that instruction is its first one, so Wdown's output features are the
+// MFMA "M" index and tokens the "N" index: a workgroup owns 256 features x 256 tokens, its four
+// wavefronts 128 x 128 each (16 accumulator blocks = all 256 accumulation registers).
+// Operand layout (checked on the GPU against a host product): a lane (row, half c) takes 8
+// consecutive stored values of its row = the dense K range 16 c .. 16 c + 15 of the instruction's
+// 32, the 16 bits of those four groups' position codes as its index operand, and from the dense
+// side K 8 c .. 8 c + 7 and 16 + 8 c .. 16 + 8 c + 7.  The compressed form of dass_compress_24
+// (groups along the columns) is exactly that: no shuffling, only addresses.
+//
+// K slabs of 64 dense columns go from global memory straight into a ring of three LDS stages
+// (buffer_load ... lds): 256 rows x 64 B of values, 256 x 8 B of codes, 256 tokens x 128 B of
+// y = 50 KB a stage.  Rows are XOR-swizzled in 16-byte chunks so that the fragment reads spread
+// over the banks.  One barrier per slab; the loads of slab s + 2 are issued right after it.
+#include "dass_internal.h"
+
+namespace dass {
+namespace sp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+constexpr int kFM = 256, kTN = 256, kBK = 64;          // features, tokens per tile; dense K per slab
+constexpr int kABytes = kFM * (kBK / 2) * 2;           // 16 KB of values
+constexpr int kMBytes = kFM * (kBK / 8);               // 2 KB of codes
+constexpr int kBBytes = kTN * kBK * 2;                 // 32 KB of y
+constexpr int kStage = kABytes + kMBytes + kBBytes;    // 50 KB
+constexpr int kStages = 3;
+constexpr int kLds = kStages * kStage;                 // 150 KB
+constexpr int kLoadsPerSlab = 4 + 2 + 8;               // wave-loads a wavefront issues per slab
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ uint32_t bf16_bits(float x)   // round to nearest even, finite inputs
+{
+    const uint32_t b = __float_as_uint(x);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+__global__ __launch_bounds__(256) void down_sparse24_kernel(
+    const uint16_t *__restrict__ Y, int64_t T, int64_t ldy, const uint16_t *__restrict__ values, int64_t ldv,
+    const uint8_t *__restrict__ meta, int64_t ldm, int64_t d, int64_t d_int, uint16_t *__restrict__ out,
+    int64_t ldo, int64_t tiles_t, int64_t tiles_f)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];   // kLds bytes
+
+    // ---- tile assignment: patches of 4 token tiles x 8 feature tiles, dealt to the 8 XCDs
+    // (workgroup b runs on XCD b % 8), as in the calibration kernel
+    constexpr int PT = 4, PF = 8;
+    const int64_t np_f = (tiles_f + PF - 1) / PF;
+    const int64_t idx = blockIdx.x / 8, within = idx % (PT * PF);
+    const int64_t patch = (idx / (PT * PF)) * 8 + blockIdx.x % 8;
+    const int64_t tile_t = (patch / np_f) * PT + within / PF, tile_f = (patch % np_f) * PF + within % PF;
+    if (tile_t >= tiles_t || tile_f >= tiles_f)
+        return;
+    const int64_t t0 = tile_t * kTN, f0 = tile_f * kFM;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;   // feature half, token half of the tile
+    const int fr = lane & 31, fc = lane >> 5;
+
+    // ---- global -> LDS.  Rows past the end of a matrix lie beyond the end of its buffer
+    // descriptor and read as zeros.
+    const int64_t rows_f = d - f0 < kFM ? d - f0 : kFM, rows_t = T - t0 < kTN ? T - t0 : kTN;
+    constexpr int kRawBuffer = 0x00020000;
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(values + f0 * ldv), 0, (int)((rows_f - 1) * ldv * 2 + d_int), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(meta + f0 * ldm), 0, (int)((rows_f - 1) * ldm + d_int / 8), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(Y + t0 * ldy), 0, (int)((rows_t - 1) * ldy * 2 + d_int * 2), kRawBuffer);
+    // values: a wave-load is 16 rows x 64 B; lane l fills slot l % 4 of row l / 4 with chunk slot ^ (row / 4 & 3)
+    uint32_t a_off[4], m_off[2], b_off[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = (wave * 4 + q) * 16 + (lane >> 2);
+        a_off[q] = (uint32_t)((int64_t)r * ldv * 2 + (((lane & 3) ^ ((r >> 2) & 3)) * 16));
+    }
+    // codes: a wave-load is 32 rows x 8 B, 4 bytes a lane
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int r = (wave * 2 + q) * 32 + (lane >> 1);
+        m_off[q] = (uint32_t)((int64_t)r * ldm + (lane & 1) * 4);
+    }
+    // y: a wave-load is 8 rows x 128 B; lane l fills slot l % 8 of row l / 8 with chunk slot ^ (row / 2 & 7)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int r = (wave * 8 + q) * 8 + (lane >> 3);
+        b_off[q] = (uint32_t)((int64_t)r * ldy * 2 + (((lane & 7) ^ ((r >> 1) & 7)) * 16));
+    }
+    auto issue_slab = [&](int s) {
+        char *st = lds + (s % kStages) * kStage;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr_t)(st + (wave * 4 + q) * 1024), 16, a_off[q],
+                                                     s * kBK, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lds_ptr_t)(st + kABytes + (wave * 2 + q) * 256), 4, m_off[q],
+                                                     s * (kBK / 8), 0, 0);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_ptr_t)(st + kABytes + kMBytes + (wave * 8 + q) * 1024), 16,
+                                                     b_off[q], s * kBK * 2, 0, 0);
+    };
+
+    // ---- LDS -> registers
+    int a_row[4], b_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        a_row[i] = wm * 128 + i * 32 + fr;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        b_row[j] = wn * 128 + j * 32 + fr;
+    struct Frags {
+        bf16x8 a[4];
+        bf16x16 b[4];
+    };
+    auto read_frags = [&](Frags &f, const char *st, int kk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = a_row[i];
+            f.a[i] = *reinterpret_cast<const bf16x8 *>(st + (r * 4 + ((2 * kk + fc) ^ ((r >> 2) & 3))) * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = b_row[j];
+            const char *row = st + kABytes + kMBytes + r * 128;
+            const int sw = (r >> 1) & 7;
+            const bf16x8 lo = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + fc) ^ sw) * 16));
+            const bf16x8 hi = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + 2 + fc) ^ sw) * 16));
+            f.b[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.0f;
+
+    const int S = (int)(d_int / kBK);   // the host guarantees d_int % 64 == 0
+    issue_slab(0);
+    if (S > 1)
+        issue_slab(1);
+    Frags fa, fb;
+    for (int s = 0; s < S; ++s) {
+        // slab s has landed (only the loads of slab s + 1 may be in flight), and after the barrier
+        // nobody reads slab s - 1 any more: its stage takes slab s + 2
+        if (s + 1 < S)
+            wait_vmcnt<kLoadsPerSlab>();
+        else
+            wait_vmcnt<0>();
+        block_barrier();
+        if (s + 2 < S)
+            issue_slab(s + 2);
+        const char *st = lds + (s % kStages) * kStage;
+        u32x2 codes[4];   // the 16 nibbles of each of this lane's four rows
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            codes[i] = *reinterpret_cast<const u32x2 *>(st + kABytes + a_row[i] * 8);
+        read_frags(fa, st, 0);
+        read_frags(fb, st, 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ix = (int)(codes[i][0] >> (16 * fc));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa.a[i], fa.b[j], acc[i][j], ix, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ix = (int)(codes[i][1] >> (16 * fc));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fb.a[i], fb.b[j], acc[i][j], ix, 0, 0);
+        }
+    }
+
+    // ---- epilogue: the tile goes to LDS as bf16 [token][feature] (row stride 528 B) and leaves it
+    // in whole 16-byte chunks of output rows.  A lane holds, per block, 4 x 4 consecutive features
+    // of one token: 8-byte writes.
+    block_barrier();   // every wavefront is done with the last slab
+    constexpr int SROW = kFM * 2 + 16;
+    static_assert(kTN * SROW <= kLds, "the tile fits in the ring");
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int token = wn * 128 + j * 32 + fr, feature = wm * 128 + i * 32 + 8 * g + 4 * fc;
+                u32x2 w;
+                w[0] = bf16_bits(acc[i][j][4 * g]) | bf16_bits(acc[i][j][4 * g + 1]) << 16;
+                w[1] = bf16_bits(acc[i][j][4 * g + 2]) | bf16_bits(acc[i][j][4 * g + 3]) << 16;
+                *reinterpret_cast<u32x2 *>(lds + token * SROW + feature * 2) = w;
+            }
+    __syncthreads();
+    constexpr int CPR = kFM / 8;   // 16-byte chunks per tile row
+    for (int c = tid; c < kTN * CPR; c += 256) {
+        const int row = c / CPR, cc = c % CPR;
+        const int64_t t = t0 + row, f = f0 + cc * 8;
+        if (t < T && f < d)   // d is a multiple of 8: a chunk is inside or outside
+            *reinterpret_cast<u32x4 *>(out + t * ldo + f) = *reinterpret_cast<const u32x4 *>(lds + row * SROW + cc * 16);
+    }
+}
+
+}  // namespace sp
+}  // namespace dass
+
+extern "C" dass_status dass_down_proj_sparse24(const void *Y, int64_t T, int64_t ldy, const void *values, int64_t ldv,
+                                               const uint8_t *meta, int64_t ldm, int64_t d, int64_t d_int,
+                                               dass_dtype dt, void *out, int64_t ldo, void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_down_proj_sparse24";
+    if (!Y || !values || !meta || !out)
+        return fail(DASS_ERR_NULL, "%s: Y, values, meta and out must not be NULL", fn);
+    if (!valid_dtype(dt))
+        return fail(DASS_ERR_DTYPE, "%s: unknown dtype %d", fn, (int)dt);
+    if (dt != DASS_BF16)
+        return fail(DASS_ERR_DTYPE, "%s: only bf16 is implemented", fn);
+    if (T <= 0 || d <= 0 || d_int <= 0)
+        return fail(DASS_ERR_SHAPE, "%s: T=%lld d=%lld d_int=%lld must be positive", fn, (long long)T, (long long)d,
+                    (long long)d_int);
+    if (d_int % 64 != 0 || d % 8 != 0)
+        return fail(DASS_ERR_SHAPE, "%s: d_int=%lld must be a multiple of 64 and d=%lld of 8", fn, (long long)d_int,
+                    (long long)d);
+    if (ldy < d_int || ldv < d_int / 2 || ldm < d_int / 8 || ldo < d)
+        return fail(DASS_ERR_SHAPE, "%s: a leading dimension is shorter than its row", fn);
+    if (!aligned16(Y) || !aligned16(values) || !aligned16(out) || (reinterpret_cast<uintptr_t>(meta) & 3u))
+        return fail(DASS_ERR_ALIGN, "%s: Y, values and out must be 16-byte aligned, meta 4-byte", fn);
+    if (ldy % 8 != 0 || ldv % 8 != 0 || ldo % 8 != 0 || ldm % 4 != 0)
+        return fail(DASS_ERR_ALIGN, "%s: ldy, ldv, ldo must be multiples of 8 elements, ldm of 4 bytes", fn);
+    // 32-bit byte offsets inside a tile's rows
+    if ((int64_t)sp::kTN * ldy * 2 >= 0x7fffffffLL || (int64_t)sp::kFM * ldv * 2 >= 0x7fffffffLL ||
+        (int64_t)sp::kFM * ldm >= 0x7fffffffLL)
+        return fail(DASS_ERR_SHAPE, "%s: rows too long for the tile addressing", fn);
+    const int64_t tiles_t = (T + sp::kTN - 1) / sp::kTN, tiles_f = (d + sp::kFM - 1) / sp::kFM;
+    const int64_t patches = (tiles_t + 3) / 4 * ((tiles_f + 7) / 8);
+    const int64_t blocks = (patches + 7) / 8 * 8 * 32;
+    if (blocks > 0x7fffffffLL)
+        return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(sp::down_sparse24_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, sp::kLds);
+    if (e != hipSuccess)
+        return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, sp::kLds, hipGetErrorString(e));
+    hipLaunchKernelGGL(sp::down_sparse24_kernel, dim3((unsigned)blocks), dim3(256), sp::kLds, stream,
+                       static_cast<const uint16_t *>(Y), T, ldy, static_cast<const uint16_t *>(values), ldv, meta, ldm,
+                       d, d_int, static_cast<uint16_t *>(out), ldo, tiles_t, tiles_f);
+    return check_launch("sparse down-projection kernel");
+}

@@ -1,0 +1,115 @@
+"""GPU parity: dass_down_proj_sparse24 (Eq. 3 from the 2:4 compressed Down-Proj on the sparse
+matrix cores) against the float64 oracle.
+
+Tolerance, derived from the arithmetic (u = 2^-8, bf16's unit roundoff; A = the sum of the
+magnitudes of the terms, from the oracle): the products are exact in f32, their f32 accumulation
+errs by at most K 2^-24 A <= 0.44 u A for K = d_int <= 28672 (worst-case linear bound), and the
+output is rounded to bf16 once: |gpu - oracle| <= u |oracle| + 0.5 u A.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_01943_amd as dass
+from paper_2405_01943_amd import synth
+
+from gpu_helpers import padded, to_np32
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(out, ref, ab, what):
+    tol = 2.0 ** -8 * (np.abs(ref) + 0.5 * ab) + 1e-30
+    err = np.abs(np.asarray(out, dtype=np.float64) - ref)
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, f"{what}: worst error / tolerance = {worst:.3f}"
+    assert float(np.mean(err / tol)) < 0.35, what
+
+
+def _sparse_weights(d, d_int, seed):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal((d, d_int)) * 0.1).astype(np.float32)
+    for row in W:
+        for g in range(d_int // 4):
+            row[4 * g + rng.choice(4, size=2, replace=False)] = 0.0
+    W[rng.random(W.shape) < 0.05] = 0.0
+    return torch.from_numpy(W).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("T,d,d_int,pad", [(300, 192, 320, 0), (513, 264, 448, 8), (256, 256, 64, 0), (70, 8, 704, 16),
+                                           (1, 520, 128, 0)])
+def test_sparse_down_small_shapes(gpu_device, T, d, d_int, pad):
+    W = _sparse_weights(d, d_int, T + d)
+    # the compressed form comes from the oracle, so the test does not lean on the GPU's compressor
+    ov, om, surplus = oracle.compress_24(W.float().numpy(), "cols")
+    assert surplus == 0
+    values = torch.from_numpy(ov).to(torch.bfloat16).to(gpu_device)
+    meta = torch.from_numpy(om).to(gpu_device)
+    g = torch.Generator(device="cpu").manual_seed(d_int)
+    Y = torch.randn((T, d_int), generator=g).to(torch.bfloat16).to(gpu_device)
+    out = torch.full((T, d), 3.0, dtype=torch.bfloat16, device=gpu_device)
+    if pad:
+        Y, values, out = padded(Y, pad), padded(values, pad), padded(out, pad)
+        big = torch.full((d, d_int // 8 + 4), 0xEE, dtype=torch.uint8, device=gpu_device)
+        big[:, :d_int // 8] = meta
+        meta = big[:, :d_int // 8]
+    dass.down_proj_sparse24(Y, values, meta, out)
+    torch.cuda.synchronize()
+    ref, ab = oracle.down_sparse24(to_np32(Y), ov, om, want_abs=True)
+    _check(to_np32(out), ref, ab, f"T={T} d={d} d_int={d_int}")
+    if pad:
+        assert torch.all(out._base[:, d:] == 7.0)
+
+
+def test_sparse_down_equals_dense_route(gpu_device):
+    """Prune, compress and multiply on the GPU, and compare with the dense down projection of
+    dass_mlp_forward's second launch on the same pruned matrix: the same sums in another order."""
+    T, d, d_int = 700, 256, 512
+    g = torch.Generator(device="cpu").manual_seed(4)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(gpu_device)
+    Wg, Wu = ((torch.randn((d_int, d), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device) for _ in range(2))
+    Wd = (torch.randn((d, d_int), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    norms = torch.rand(d_int, generator=g).to(gpu_device) + 0.5
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    values = torch.empty((d, d_int // 2), dtype=torch.bfloat16, device=gpu_device)
+    meta = torch.empty((d, d_int // 8), dtype=torch.uint8, device=gpu_device)
+    dass.compress_24(Wd, "cols", values, meta)
+    dense = torch.empty((T, d), dtype=torch.bfloat16, device=gpu_device)
+    ws = torch.empty(dass.mlp_forward_workspace_bytes(T, d, d_int), dtype=torch.uint8, device=gpu_device)
+    dass.mlp_forward(X, Wg, Wu, Wd, "silu", dense, workspace=ws)
+    Y = ws.view(torch.bfloat16).view(T, d_int)          # the y that the dense route multiplied
+    sparse = torch.empty_like(dense)
+    dass.down_proj_sparse24(Y, values, meta, sparse)
+    torch.cuda.synchronize()
+    ref, ab = oracle.down_sparse24(to_np32(Y), to_np32(values), meta.cpu().numpy(), want_abs=True)
+    _check(to_np32(sparse), ref, ab, "sparse route")
+    _check(to_np32(dense), ref, ab, "dense route")
+
+
+def test_sparse_down_full_size(gpu_device):
+    """LLaMA2-7B-shaped Down-Proj with DaSS 2:4 weights, 32768 tokens, sampled tokens against the
+    oracle (first, last, both sides of tile boundaries, seeded random ones)."""
+    cfg = synth.CONFIGS["llama2_7b"]
+    dev = gpu_device
+    T, d, d_int = 32768, cfg.d, cfg.d_int
+    Wd = synth.make_weight(cfg, "wd", dev)
+    norms = synth.make_norms(d_int, dev)
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    values = torch.empty((d, d_int // 2), dtype=Wd.dtype, device=dev)
+    meta = torch.empty((d, d_int // 8), dtype=torch.uint8, device=dev)
+    surplus = torch.zeros(1, dtype=torch.int64, device=dev)
+    dass.compress_24(Wd, "cols", values, meta, surplus)
+    g = torch.Generator(device=dev).manual_seed(1)
+    Y = torch.randn((T, d_int), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    dass.down_proj_sparse24(Y, values, meta, out)
+    torch.cuda.synchronize()
+    assert int(surplus.item()) == 0
+    rng = np.random.default_rng(0)
+    tokens = np.unique(np.concatenate([[0, 1, 255, 256, 257, 1023, 1024, T - 257, T - 256, T - 1],
+                                       rng.integers(0, T, size=14)]))
+    sel = torch.as_tensor(tokens, device=dev)
+    ref, ab = oracle.down_sparse24(to_np32(Y[sel]), to_np32(values), meta.cpu().numpy(), want_abs=True)
+    _check(to_np32(out[sel]), ref, ab, "7B shape")
+    assert torch.isfinite(out.float()).all()

@@ -190,3 +190,22 @@ def test_compress_rejections(lib):
     assert _cmp(lib, ldv=34) == "DASS_ERR_ALIGN"
     assert _cmp(lib, surplus=ODD) == "DASS_ERR_ALIGN"
     assert _cmp(lib, V=FAKE) == "DASS_ERR_ARG"                                 # values_out on top of W
+
+
+def _spd(lib, Y=FAKE, T=256, ldy=192, V=FAKE2, ldv=96, M=FAKE3, ldm=24, d=128, d_int=192, dt=1, out=FAKE, ldo=128):
+    return lib.dass_status_string(lib.dass_down_proj_sparse24(Y, T, ldy, V, ldv, M, ldm, d, d_int, dt, out, ldo,
+                                                              None)).decode()
+
+
+def test_sparse_down_rejections(lib):
+    assert _spd(lib, Y=None) == "DASS_ERR_NULL"
+    assert _spd(lib, M=None) == "DASS_ERR_NULL"
+    assert _spd(lib, dt=0) == "DASS_ERR_DTYPE"
+    assert _spd(lib, T=0) == "DASS_ERR_SHAPE"
+    assert _spd(lib, d_int=200, ldy=200, ldv=104, ldm=28) == "DASS_ERR_SHAPE"   # d_int % 64
+    assert _spd(lib, d=100) == "DASS_ERR_SHAPE"                                # d % 8
+    assert _spd(lib, ldv=88) == "DASS_ERR_SHAPE"
+    assert _spd(lib, ldm=20) == "DASS_ERR_SHAPE"
+    assert _spd(lib, V=ODD) == "DASS_ERR_ALIGN"
+    assert _spd(lib, ldm=26) == "DASS_ERR_ALIGN"
+    assert _spd(lib, ldo=132) == "DASS_ERR_ALIGN"
