@@ -294,7 +294,22 @@ def main():
             if it >= 1:
                 f_ms.append(a.elapsed_time(b))
         f_ms = statistics.median(f_ms)
-        del ws_f, nxt
+        # Eq. 3 alone from the compressed Down-Proj on the sparse MFMA, on the y the forward pass left
+        Yb = ws_f.view(Wg.dtype).view(T, I)
+        sp_vals = torch.empty((d, I // 2), dtype=Wg.dtype, device=dev)
+        sp_meta = torch.empty((d, I // 8), dtype=torch.uint8, device=dev)
+        dass.compress_24(pruned[2], "cols", sp_vals, sp_meta)
+        sp_ms = []
+        for it in range(4):
+            a, b = ev(), ev()
+            a.record()
+            dass.down_proj_sparse24(Yb, sp_vals, sp_meta, nxt)
+            b.record()
+            torch.cuda.synchronize()
+            if it >= 1:
+                sp_ms.append(a.elapsed_time(b))
+        sp_ms = statistics.median(sp_ms)
+        del ws_f, nxt, Yb, sp_vals, sp_meta
         cmp_us = {}
         for name, w, axis in (("down_cols", pruned[2], "cols"), ("gate_rows", pruned[0], "rows")):
             rows, cols = w.shape
@@ -316,6 +331,8 @@ def main():
         cmp_bytes = Wd.numel() * (esz + esz / 2.0 + 0.125)   # read W, write half of it and 1 bit per weight
         chain = {"mlp_forward_ms": f_ms, "mlp_forward_TFLOPs": 6.0 * T * d * I / (f_ms * 1e-3) / 1e12,
                  "mlp_forward_frac_of_mfma_peak": 6.0 * T * d * I / (f_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                 "down_proj_sparse24_ms": sp_ms,
+                 "down_proj_sparse24_dense_equivalent_TFLOPs": 2.0 * T * d * I / (sp_ms * 1e-3) / 1e12,
                  "compress_24_us": cmp_us, "compress_24_bytes": cmp_bytes,
                  "compress_24_GBps": {k: cmp_bytes / (v * 1e-6) / 1e9 for k, v in cmp_us.items()}}
         del pruned

@@ -105,20 +105,23 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         const int r = (wave * 8 + q) * 8 + (lane >> 3);
         b_off[q] = (uint32_t)((int64_t)r * ldy * 2 + (((lane & 7) ^ ((r >> 1) & 7)) * 16));
     }
-    auto issue_slab = [&](int s) {
+    // q-th of the 14 wave-loads a wavefront issues for slab s: 4 of values, 2 of codes, 8 of y
+    auto load_one = [&](int s, int q) {
         char *st = lds + (s % kStages) * kStage;
+        if (q < 4)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr_t)(st + (wave * 4 + q) * 1024), 16, a_off[q], s * kBK, 0,
+                                                     0);
+        else if (q < 6)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lds_ptr_t)(st + kABytes + (wave * 2 + q - 4) * 256), 4,
+                                                     m_off[q - 4], s * (kBK / 8), 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_ptr_t)(st + kABytes + kMBytes + (wave * 8 + q - 6) * 1024),
+                                                     16, b_off[q - 6], s * kBK * 2, 0, 0);
+    };
+    auto issue_slab = [&](int s) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr_t)(st + (wave * 4 + q) * 1024), 16, a_off[q],
-                                                     s * kBK, 0, 0);
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lds_ptr_t)(st + kABytes + (wave * 2 + q) * 256), 4, m_off[q],
-                                                     s * (kBK / 8), 0, 0);
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_ptr_t)(st + kABytes + kMBytes + (wave * 8 + q) * 1024), 16,
-                                                     b_off[q], s * kBK * 2, 0, 0);
+        for (int q = 0; q < kLoadsPerSlab; ++q)
+            load_one(s, q);
     };
 
     // ---- LDS -> registers
@@ -130,24 +133,26 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
     for (int j = 0; j < 4; ++j)
         b_row[j] = wn * 128 + j * 32 + fr;
     struct Frags {
-        bf16x8 a[4];
-        bf16x16 b[4];
+        bf16x8 a[4], lo[4], hi[4];   // the dense operand of block j is lo[j] followed by hi[j]
     };
-    auto read_frags = [&](Frags &f, const char *st, int kk) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = a_row[i];
-            f.a[i] = *reinterpret_cast<const bf16x8 *>(st + (r * 4 + ((2 * kk + fc) ^ ((r >> 2) & 3))) * 16);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = b_row[j];
+    // q-th of the 12 fragment reads of K step kk of the slab in stage st: 4 sparse, 8 dense halves
+    auto read_one = [&](Frags &f, const char *st, int kk, int q) {
+        if (q < 4) {
+            const int r = a_row[q];
+            f.a[q] = *reinterpret_cast<const bf16x8 *>(st + (r * 4 + ((2 * kk + fc) ^ ((r >> 2) & 3))) * 16);
+        } else {
+            const int j = (q - 4) >> 1, r = b_row[j];
             const char *row = st + kABytes + kMBytes + r * 128;
             const int sw = (r >> 1) & 7;
-            const bf16x8 lo = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + fc) ^ sw) * 16));
-            const bf16x8 hi = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + 2 + fc) ^ sw) * 16));
-            f.b[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+            if ((q & 1) == 0)
+                f.lo[j] = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + fc) ^ sw) * 16));
+            else
+                f.hi[j] = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + 2 + fc) ^ sw) * 16));
         }
+    };
+    u32x2 codes[4], codes_next[4];   // the 16 nibbles of a slab of each of this lane's four rows
+    auto read_codes = [&](u32x2 *c, const char *st, int i) {
+        c[i] = *reinterpret_cast<const u32x2 *>(st + kABytes + a_row[i] * 8);
     };
 
     f32x16 acc[4][4];
@@ -158,43 +163,69 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.0f;
+    auto mfma = [&](const Frags &f, const u32x2 *c, int kk, int q) {
+        const int i = q >> 2, j = q & 3;
+        const bf16x16 b = __builtin_shufflevector(f.lo[j], f.hi[j], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i], b, acc[i][j], (int)(c[i][kk] >> (16 * fc)), 0, 0);
+    };
 
+    // ---- main loop.  A slab is two K steps of 16 sparse MFMAs.  Under the MFMAs of K step 0 go
+    // the fragment reads of K step 1; then one barrier - slab s + 1 has landed, nobody reads slab
+    // s from LDS any more, so its stage takes slab s + 3 - and under the MFMAs of K step 1 go those
+    // 14 loads and the fragment reads of K step 0 of slab s + 1.
     const int S = (int)(d_int / kBK);   // the host guarantees d_int % 64 == 0
     issue_slab(0);
     if (S > 1)
         issue_slab(1);
+    if (S > 2)
+        issue_slab(2);
+    if (S > 2)
+        wait_vmcnt<2 * kLoadsPerSlab>();
+    else if (S > 1)
+        wait_vmcnt<kLoadsPerSlab>();
+    else
+        wait_vmcnt<0>();
+    block_barrier();
     Frags fa, fb;
+#pragma unroll
+    for (int q = 0; q < 12; ++q)
+        read_one(fa, lds, 0, q);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        read_codes(codes, lds, i);
     for (int s = 0; s < S; ++s) {
-        // slab s has landed (only the loads of slab s + 1 may be in flight), and after the barrier
-        // nobody reads slab s - 1 any more: its stage takes slab s + 2
-        if (s + 1 < S)
-            wait_vmcnt<kLoadsPerSlab>();
-        else
-            wait_vmcnt<0>();
-        block_barrier();
+        const char *st = lds + (s % kStages) * kStage, *st_next = lds + ((s + 1) % kStages) * kStage;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {   // K step 0
+            if (q < 12)
+                read_one(fb, st, 1, q);
+            mfma(fa, codes, 0, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // slab s + 1 has landed (only slab s + 2 may be in flight) and this wavefront holds its last
+        // fragments of slab s: vmcnt(14 or 0), lgkmcnt(0)
         if (s + 2 < S)
-            issue_slab(s + 2);
-        const char *st = lds + (s % kStages) * kStage;
-        u32x2 codes[4];   // the 16 nibbles of each of this lane's four rows
+            __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerSlab);
+        else
+            __builtin_amdgcn_s_waitcnt(0x0070);
+        block_barrier();
+        const bool more = s + 1 < S, load = s + 3 < S;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {   // K step 1
+            if (load && q < kLoadsPerSlab)
+                load_one(s + 3, q);
+            if (more) {
+                if (q < 12)
+                    read_one(fa, st_next, 0, q);
+                else
+                    read_codes(codes_next, st_next, q - 12);
+            }
+            mfma(fb, codes, 1, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            codes[i] = *reinterpret_cast<const u32x2 *>(st + kABytes + a_row[i] * 8);
-        read_frags(fa, st, 0);
-        read_frags(fb, st, 1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int ix = (int)(codes[i][0] >> (16 * fc));
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa.a[i], fa.b[j], acc[i][j], ix, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int ix = (int)(codes[i][1] >> (16 * fc));
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fb.a[i], fb.b[j], acc[i][j], ix, 0, 0);
-        }
+            codes[i] = codes_next[i];
     }
 
     // ---- epilogue: the tile goes to LDS as bf16 [token][feature] (row stride 528 B) and leaves it
