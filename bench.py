@@ -38,7 +38,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; see profiles/).  A figure only stands while the source
 # of its kernel is the one the counters were taken on; otherwise `traffic` is null.
 MEASURED_TRAFFIC = {
-    "stage1": {"sources": ("calib.hip",), "sha256": "f17f67ce7499f68ef5010c6420366c9db0a48053455389ed618e4c9278bcd29a",
+    "stage1": {"sources": ("calib.hip",), "sha256": "c91cff94c0044d4e126404664ad304045625fdc8e9be339734a43a01216adf56",
                "bytes": (35490500 * 2.0 + 88064) * 1024},
     "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "021c3339f721ba7bacecafc3bc608e59d0edb8307e2673071fa1762e4faa73b7",
                "bytes": (2 * (44423.5 * 2.0 + 88070.0) + (44526.5 * 2.0 + 88065.0)) * 1024},

@@ -12,10 +12,15 @@
 // index, so the 16 accumulator registers a lane holds for one 32x32 block belong
 // to ONE neuron and 16 tokens: the sum over tokens starts as plain register
 // adds, then one cross-lane add, then one f32 atomic per neuron and wavefront.
-//   calib_pipe_kernel  d a multiple of 32: slabs go from global memory straight
-//                      into a four-deep LDS ring (no register staging), and the
-//                      loads, the fragment reads and the MFMAs of consecutive
-//                      slabs are interleaved by hand.
+//   calib_pipe64_kernel  d a multiple of 64 (every model shape): slabs of 64
+//                      columns go from global memory straight into a ring of
+//                      five 32 KB LDS units (no register staging), whole
+//                      128-byte lines per request; loads, fragment reads and
+//                      MFMAs of consecutive slabs are interleaved by hand.  The
+//                      same main loop also serves Eq. 2 + Eq. 3 themselves
+//                      (dass_mlp_forward) through two storing epilogues.
+//   calib_pipe_kernel  d a multiple of 32: the same with 32-column slabs in a
+//                      four-deep ring.
 //   calib_mfma_kernel  any d that is a multiple of 8: register-staged,
 //                      double-buffered; the K tail is masked.
 //
