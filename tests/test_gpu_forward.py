@@ -95,3 +95,39 @@ def test_forward_full_size_with_pruned_weights(gpu_device):
                                  to_np32(Wd), cfg.act, want_abs=True)
     _check(to_np32(out[torch.as_tensor(tokens, device=dev)]), ref, ab, "7B shape, 2:4 weights")
     assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("name", ["mistral_7b", "gemma_7b", "llama2_13b", "llama2_70b"])
+def test_forward_other_model_shapes(gpu_device, name):
+    """The other model shapes (tanh-GELU for the Gemma one; Gate + Up beyond the 256 MB cache for
+    Gemma and 70B, which switches the tile order), a ragged token count, sampled tokens."""
+    cfg = synth.CONFIGS[name]
+    dev = gpu_device
+    T, d, d_int = 1024 + 77, cfg.d, cfg.d_int
+    X = synth.make_x(cfg, 0, T, dev)
+    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
+    out = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    dass.mlp_forward(X, Wg, Wu, Wd, cfg.act, out)
+    # and Eq. 3 again from the compressed 2:4 Down-Proj, on the y the call left in its workspace
+    ws = torch.empty(dass.mlp_forward_workspace_bytes(T, d, d_int), dtype=torch.uint8, device=dev)
+    norms = synth.make_norms(d_int, dev)
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    out2 = torch.empty_like(out)
+    dass.mlp_forward(X, Wg, Wu, Wd, cfg.act, out2, workspace=ws)
+    values = torch.empty((d, d_int // 2), dtype=Wd.dtype, device=dev)
+    meta = torch.empty((d, d_int // 8), dtype=torch.uint8, device=dev)
+    dass.compress_24(Wd, "cols", values, meta)
+    Y = ws.view(torch.bfloat16).view(T, d_int)
+    out3 = torch.empty_like(out)
+    dass.down_proj_sparse24(Y, values, meta, out3)
+    torch.cuda.synchronize()
+    tokens = np.array([0, 255, 256, 1023, 1024, T - 1])
+    sel = torch.as_tensor(tokens, device=dev)
+    Wd_dense = synth.make_weight(cfg, "wd", dev)
+    ref, ab = oracle.mlp_forward(to_np32(X[sel]), to_np32(Wg), to_np32(Wu), to_np32(Wd_dense), cfg.act, want_abs=True)
+    _check(to_np32(out[sel]), ref, ab, f"{name}, dense weights")
+    ref2, ab2 = oracle.mlp_forward(to_np32(X[sel]), to_np32(Wg), to_np32(Wu), to_np32(Wd), cfg.act, want_abs=True)
+    _check(to_np32(out2[sel]), ref2, ab2, f"{name}, 2:4 Down-Proj")
+    ref3, ab3 = oracle.down_sparse24(to_np32(Y[sel]), to_np32(values), meta.cpu().numpy(), want_abs=True)
+    err = np.abs(to_np32(out3[sel]).astype(np.float64) - ref3) / (2.0 ** -8 * (np.abs(ref3) + 0.5 * ab3) + 1e-30)
+    assert float(err.max()) <= 1.0, f"{name}: sparse route at {err.max():.2f} of its tolerance"
