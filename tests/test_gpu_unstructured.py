@@ -216,6 +216,33 @@ def test_unstructured_long_column_lines(gpu_device, dtype, rows, cols, pad):
             assert np.array_equal(mask.cpu().numpy(), want_mask)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+def test_unstructured_threshold_among_zero_scores(gpu_device, dtype, axes):
+    """More than half of every line scores zero (weights already pruned, or dead neurons with norm
+    0) and fewer than that are to be pruned: the threshold is 0, every nonzero score is kept and
+    the zeros are decided by their index."""
+    rows, cols = (3000, 64) if axes[1] == "rows" else (40, 3000 * 8 // 8)
+    g = torch.Generator(device="cpu").manual_seed(17)
+    W = (torch.randn((rows, cols), generator=g) * 0.02)
+    W[torch.rand((rows, cols), generator=g) < 0.6] = 0.0
+    W = W.to(dtype).to(gpu_device)
+    n = rows if axes[0] == "rows" else cols
+    nrm = synth.make_norms(n, "cpu", 5)
+    nrm[::7] = 0.0                      # dead neurons on top
+    nrm = nrm.to(gpu_device)
+    length = rows if axes[1] == "rows" else cols
+    for alpha, n_prune in ((1.0, length // 3), (0.5, length // 2), (0.0, length // 4)):
+        Wc = W.clone()
+        want, want_mask = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), axes[0], axes[1], alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(Wc, nrm, axes[0], axes[1], alpha, n_prune, mask_out=mask)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), f"alpha={alpha}: {first_mismatch(Wc, want)}"
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
