@@ -98,4 +98,4 @@ extern "C" const char *dass_status_string(dass_status s)
 
 extern "C" const char *dass_last_error_string(void) { return dass::error_buffer(); }
 
-extern "C" int dass_version(void) { return 103; }  // 1.3: input norms, MLP output, 2:4 storage form, sparse down projection
+extern "C" int dass_version(void) { return 300; }  // 0.3.0: input norms, MLP output, 2:4 storage form, sparse down projection
