@@ -16,6 +16,8 @@
 // over the banks.  One barrier per slab; the loads of slab s + 2 are issued right after it.
 #include "dass_internal.h"
 
+#include <type_traits>
+
 namespace dass {
 namespace sp {
 
@@ -193,7 +195,11 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         read_codes(codes, lds, i);
-    for (int s = 0; s < S; ++s) {
+    // MORE: a slab follows; LOAD: slab s + 3 exists; AHEAD: slab s + 2 exists (it may be in flight
+    // at the barrier).  All three are compile-time: the steady state has no branch between MFMAs.
+    auto slab_body = [&](int s, auto more_tag, auto load_tag, auto ahead_tag) {
+        constexpr bool MORE = decltype(more_tag)::value, LOAD = decltype(load_tag)::value,
+                       AHEAD = decltype(ahead_tag)::value;
         const char *st = lds + (s % kStages) * kStage, *st_next = lds + ((s + 1) % kStages) * kStage;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {   // K step 0
@@ -204,17 +210,16 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         }
         // slab s + 1 has landed (only slab s + 2 may be in flight) and this wavefront holds its last
         // fragments of slab s: vmcnt(14 or 0), lgkmcnt(0)
-        if (s + 2 < S)
+        if (AHEAD)
             __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerSlab);
         else
             __builtin_amdgcn_s_waitcnt(0x0070);
         block_barrier();
-        const bool more = s + 1 < S, load = s + 3 < S;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {   // K step 1
-            if (load && q < kLoadsPerSlab)
+            if (LOAD && q < kLoadsPerSlab)
                 load_one(s + 3, q);
-            if (more) {
+            if (MORE) {
                 if (q < 12)
                     read_one(fa, st_next, 0, q);
                 else
@@ -223,10 +228,22 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
             mfma(fb, codes, 1, q);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (MORE) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            codes[i] = codes_next[i];
-    }
+            for (int i = 0; i < 4; ++i)
+                codes[i] = codes_next[i];
+        }
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    int s = 0;
+    for (; s + 3 < S; ++s)
+        slab_body(s, Yes{}, Yes{}, Yes{});
+    if (s + 2 < S)
+        slab_body(s++, Yes{}, No{}, Yes{});   // slab S - 3
+    if (s + 1 < S)
+        slab_body(s++, Yes{}, No{}, No{});    // slab S - 2
+    slab_body(s, No{}, No{}, No{});           // slab S - 1
 
     // ---- epilogue: the tile goes to LDS as bf16 [token][feature] (row stride 528 B) and leaves it
     // in whole 16-byte chunks of output rows.  A lane holds, per block, 4 x 4 consecutive features
