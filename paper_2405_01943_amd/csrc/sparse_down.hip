@@ -11,8 +11,9 @@
 // (groups along the columns) is exactly that: no shuffling, only addresses.
 //
 // K slabs of 64 dense columns go from global memory straight into a ring of three LDS stages
-// (buffer_load ... lds): 256 rows x 64 B of values, 256 x 8 B of codes, 256 tokens x 128 B of
-// y = 50 KB a stage.  Rows are XOR-swizzled in 16-byte chunks so that the fragment reads spread
+// (buffer_load ... lds): 256 rows x 64 B of values and 256 tokens x 128 B of y = 48 KB a stage;
+// the codes come two slabs at a time (256 rows x 16 B, two 4 KB blocks behind the ring), so that
+// a lane fetches 16 bytes of them, not 4.  Rows are XOR-swizzled in 16-byte chunks so that the fragment reads spread
 // over the banks.  One barrier per slab; the loads of slab s + 2 are issued right after it.
 #include "dass_internal.h"
 
@@ -30,12 +31,15 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 constexpr int kFM = 256, kTN = 256, kBK = 64;          // features, tokens per tile; dense K per slab
 constexpr int kABytes = kFM * (kBK / 2) * 2;           // 16 KB of values
-constexpr int kMBytes = kFM * (kBK / 8);               // 2 KB of codes
 constexpr int kBBytes = kTN * kBK * 2;                 // 32 KB of y
-constexpr int kStage = kABytes + kMBytes + kBBytes;    // 50 KB
+constexpr int kStage = kABytes + kBBytes;              // 48 KB
 constexpr int kStages = 3;
-constexpr int kLds = kStages * kStage;                 // 150 KB
-constexpr int kLoadsPerSlab = 4 + 2 + 8;               // wave-loads a wavefront issues per slab
+constexpr int kMBlock = kFM * 16;                      // codes of two slabs (128 dense K): 16 B a row, 4 KB
+constexpr int kMBase = kStages * kStage;               // two such blocks behind the ring
+constexpr int kLds = kMBase + 2 * kMBlock;             // 152 KB
+// wave-loads a wavefront issues for slab s: 4 of values, 8 of y, and with every even slab the
+// codes of that slab and the next
+constexpr int kLoadsOdd = 12, kLoadsEven = 13;
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -89,41 +93,39 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(Y + t0 * ldy), 0, (int)((rows_t - 1) * ldy * 2 + d_int * 2), kRawBuffer);
     // values: a wave-load is 16 rows x 64 B; lane l fills slot l % 4 of row l / 4 with chunk slot ^ (row / 4 & 3)
-    uint32_t a_off[4], m_off[2], b_off[8];
+    uint32_t a_off[4], m_off, b_off[8];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int r = (wave * 4 + q) * 16 + (lane >> 2);
         a_off[q] = (uint32_t)((int64_t)r * ldv * 2 + (((lane & 3) ^ ((r >> 2) & 3)) * 16));
     }
-    // codes: a wave-load is 32 rows x 8 B, 4 bytes a lane
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int r = (wave * 2 + q) * 32 + (lane >> 1);
-        m_off[q] = (uint32_t)((int64_t)r * ldm + (lane & 1) * 4);
-    }
+    // codes: a wave-load is 64 rows x 16 B (two slabs), one row a lane
+    m_off = (uint32_t)((int64_t)(wave * 64 + lane) * ldm);
     // y: a wave-load is 8 rows x 128 B; lane l fills slot l % 8 of row l / 8 with chunk slot ^ (row / 2 & 7)
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         const int r = (wave * 8 + q) * 8 + (lane >> 3);
         b_off[q] = (uint32_t)((int64_t)r * ldy * 2 + (((lane & 7) ^ ((r >> 1) & 7)) * 16));
     }
-    // q-th of the 14 wave-loads a wavefront issues for slab s: 4 of values, 2 of codes, 8 of y
+    // q-th wave-load of slab s: 0..3 values, 4..11 y, 12 (even slabs only) the codes of slabs s, s + 1
     auto load_one = [&](int s, int q) {
         char *st = lds + (s % kStages) * kStage;
         if (q < 4)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr_t)(st + (wave * 4 + q) * 1024), 16, a_off[q], s * kBK, 0,
                                                      0);
-        else if (q < 6)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lds_ptr_t)(st + kABytes + (wave * 2 + q - 4) * 256), 4,
-                                                     m_off[q - 4], s * (kBK / 8), 0, 0);
+        else if (q < 12)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_ptr_t)(st + kABytes + (wave * 8 + q - 4) * 1024), 16,
+                                                     b_off[q - 4], s * kBK * 2, 0, 0);
         else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_ptr_t)(st + kABytes + kMBytes + (wave * 8 + q - 6) * 1024),
-                                                     16, b_off[q - 6], s * kBK * 2, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lds_ptr_t)(lds + kMBase + ((s >> 1) & 1) * kMBlock + wave * 1024),
+                                                     16, m_off, (s >> 1) * 16, 0, 0);
     };
-    auto issue_slab = [&](int s) {
+    auto issue_slab = [&](int s) {   // prologue only
 #pragma unroll
-        for (int q = 0; q < kLoadsPerSlab; ++q)
+        for (int q = 0; q < kLoadsOdd; ++q)
             load_one(s, q);
+        if ((s & 1) == 0)
+            load_one(s, kLoadsOdd);
     };
 
     // ---- LDS -> registers
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
             f.a[q] = *reinterpret_cast<const bf16x8 *>(st + (r * 4 + ((2 * kk + fc) ^ ((r >> 2) & 3))) * 16);
         } else {
             const int j = (q - 4) >> 1, r = b_row[j];
-            const char *row = st + kABytes + kMBytes + r * 128;
+            const char *row = st + kABytes + r * 128;
             const int sw = (r >> 1) & 7;
             if ((q & 1) == 0)
                 f.lo[j] = *reinterpret_cast<const bf16x8 *>(row + (((4 * kk + fc) ^ sw) * 16));
@@ -153,8 +155,8 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         }
     };
     u32x2 codes[4], codes_next[4];   // the 16 nibbles of a slab of each of this lane's four rows
-    auto read_codes = [&](u32x2 *c, const char *st, int i) {
-        c[i] = *reinterpret_cast<const u32x2 *>(st + kABytes + a_row[i] * 8);
+    auto read_codes = [&](u32x2 *c, int s, int i) {   // slab s: half s % 2 of the row's 16 bytes in block s / 2
+        c[i] = *reinterpret_cast<const u32x2 *>(lds + kMBase + ((s >> 1) & 1) * kMBlock + a_row[i] * 16 + (s & 1) * 8);
     };
 
     f32x16 acc[4][4];
@@ -182,9 +184,9 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
     if (S > 2)
         issue_slab(2);
     if (S > 2)
-        wait_vmcnt<2 * kLoadsPerSlab>();
+        wait_vmcnt<kLoadsOdd + kLoadsEven>();   // slabs 1 and 2 may be in flight
     else if (S > 1)
-        wait_vmcnt<kLoadsPerSlab>();
+        wait_vmcnt<kLoadsOdd>();
     else
         wait_vmcnt<0>();
     block_barrier();
@@ -194,12 +196,18 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         read_one(fa, lds, 0, q);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        read_codes(codes, lds, i);
+        read_codes(codes, 0, i);
     // MORE: a slab follows; LOAD: slab s + 3 exists; AHEAD: slab s + 2 exists (it may be in flight
     // at the barrier).  All three are compile-time: the steady state has no branch between MFMAs.
-    auto slab_body = [&](int s, auto more_tag, auto load_tag, auto ahead_tag) {
+    // PAR: the parity of s (0, 1), which says how many loads slabs s + 2 and s + 3 are, or 2 when it
+    // is only known at run time (the last slabs): then the barrier waits as if slab s + 2 were the
+    // shorter kind (one load more has to land, harmless) and the codes' load is a run-time test.
+    auto slab_body = [&](int s, auto more_tag, auto load_tag, auto ahead_tag, auto par_tag) {
         constexpr bool MORE = decltype(more_tag)::value, LOAD = decltype(load_tag)::value,
                        AHEAD = decltype(ahead_tag)::value;
+        constexpr int PAR = decltype(par_tag)::value;
+        constexpr int kAhead = PAR == 0 ? kLoadsEven : kLoadsOdd;                    // loads of slab s + 2
+        constexpr int kIssue = PAR == 1 ? kLoadsEven : kLoadsOdd;                    // loads of slab s + 3
         const char *st = lds + (s % kStages) * kStage, *st_next = lds + ((s + 1) % kStages) * kStage;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {   // K step 0
@@ -211,19 +219,21 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         // slab s + 1 has landed (only slab s + 2 may be in flight) and this wavefront holds its last
         // fragments of slab s: vmcnt(14 or 0), lgkmcnt(0)
         if (AHEAD)
-            __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerSlab);
+            __builtin_amdgcn_s_waitcnt(0x0070 | kAhead);
         else
             __builtin_amdgcn_s_waitcnt(0x0070);
         block_barrier();
 #pragma unroll
         for (int q = 0; q < 16; ++q) {   // K step 1
-            if (LOAD && q < kLoadsPerSlab)
+            if (LOAD && q < kIssue)
                 load_one(s + 3, q);
+            if (LOAD && PAR == 2 && q == kLoadsOdd && ((s + 3) & 1) == 0)   // uniform
+                load_one(s + 3, kLoadsOdd);
             if (MORE) {
                 if (q < 12)
                     read_one(fa, st_next, 0, q);
                 else
-                    read_codes(codes_next, st_next, q - 12);
+                    read_codes(codes_next, s + 1, q - 12);
             }
             mfma(fb, codes, 1, q);
             __builtin_amdgcn_sched_barrier(0);
@@ -236,14 +246,21 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
     };
     using Yes = std::true_type;
     using No = std::false_type;
+    using Even = std::integral_constant<int, 0>;
+    using Odd = std::integral_constant<int, 1>;
+    using Any = std::integral_constant<int, 2>;
     int s = 0;
-    for (; s + 3 < S; ++s)
-        slab_body(s, Yes{}, Yes{}, Yes{});
+    for (; s + 4 < S; s += 2) {   // s is even here
+        slab_body(s, Yes{}, Yes{}, Yes{}, Even{});
+        slab_body(s + 1, Yes{}, Yes{}, Yes{}, Odd{});
+    }
+    if (s + 3 < S)
+        slab_body(s++, Yes{}, Yes{}, Yes{}, Any{});   // slab S - 4 when the loop left it
     if (s + 2 < S)
-        slab_body(s++, Yes{}, No{}, Yes{});   // slab S - 3
+        slab_body(s++, Yes{}, No{}, Yes{}, Any{});    // slab S - 3
     if (s + 1 < S)
-        slab_body(s++, Yes{}, No{}, No{});    // slab S - 2
-    slab_body(s, No{}, No{}, No{});           // slab S - 1
+        slab_body(s++, Yes{}, No{}, No{}, Any{});     // slab S - 2
+    slab_body(s, No{}, No{}, No{}, Any{});            // slab S - 1
 
     // ---- epilogue: the tile goes to LDS as bf16 [token][feature] (row stride 528 B) and leaves it
     // in whole 16-byte chunks of output rows.  A lane holds, per block, 4 x 4 consecutive features
