@@ -234,6 +234,9 @@ dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, in
  * must be multiples of 64 (DASS_ERR_SHAPE), pointers 16-byte aligned and
  * leading dimensions multiples of 8 (DASS_ERR_ALIGN).  Two launches on
  * hip_stream; nothing is allocated.
+ * Wdown may be NULL: then only Eq. 2 runs and y is left in the workspace as
+ * [T, d_int] row-major (out, ldd and ldo are not looked at) - the input of
+ * dass_down_proj_sparse24 below.
  */
 size_t dass_mlp_forward_workspace_bytes(int64_t T, int64_t d, int64_t d_int, dass_dtype dt);
 

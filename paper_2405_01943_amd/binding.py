@@ -192,19 +192,30 @@ def mlp_forward_workspace_bytes(T: int, d: int, d_int: int, dtype=torch.bfloat16
     return int(load_library().dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[dtype]))
 
 
-def mlp_forward(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, Wdown: torch.Tensor, act: str,
-                out: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
-    """dass_mlp_forward: out = (act(X Wgate^T) * (X Wup^T)) Wdown^T (Eq. 2 then Eq. 3)."""
+def mlp_forward(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, Wdown: Optional[torch.Tensor], act: str,
+                out: Optional[torch.Tensor], workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dass_mlp_forward: out = (act(X Wgate^T) * (X Wup^T)) Wdown^T (Eq. 2 then Eq. 3).
+
+    With ``Wdown=None`` only Eq. 2 runs: y is left in ``workspace`` (required then) as [T, d_int].
+    """
     lib = load_library()
     T, d, ldx = _matrix(X, "X")
     d_int, d2, ldw = _matrix(Wgate, "Wgate")
     if _matrix(Wup, "Wup") != (d_int, d2, ldw) or d2 != d:
         raise ValueError("Wgate and Wup must be [d_int, d] with one leading dimension")
-    dd, di, ldd = _matrix(Wdown, "Wdown")
-    To, do, ldo = _matrix(out, "out")
-    if (dd, di) != (d, d_int) or (To, do) != (T, d):
-        raise ValueError("Wdown must be [d, d_int] and out [T, d]")
-    if len({X.dtype, Wgate.dtype, Wup.dtype, Wdown.dtype, out.dtype}) != 1:
+    ldd = ldo = 0
+    if Wdown is None:
+        if workspace is None:
+            raise ValueError("Wdown=None leaves y in the workspace: pass one")
+        out = None
+        dtypes = {X.dtype, Wgate.dtype, Wup.dtype}
+    else:
+        dd, di, ldd = _matrix(Wdown, "Wdown")
+        To, do, ldo = _matrix(out, "out")
+        if (dd, di) != (d, d_int) or (To, do) != (T, d):
+            raise ValueError("Wdown must be [d, d_int] and out [T, d]")
+        dtypes = {X.dtype, Wgate.dtype, Wup.dtype, Wdown.dtype, out.dtype}
+    if len(dtypes) != 1:
         raise TypeError("X, the weights and out must share one dtype")
     if workspace is None:
         workspace = _scratch(int(lib.dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[X.dtype])), X.device)

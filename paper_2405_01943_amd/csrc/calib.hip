@@ -1203,8 +1203,9 @@ extern "C" dass_status dass_mlp_forward(const void *X, int64_t T, int64_t ldx, c
 {
     using namespace dass;
     const char *fn = "dass_mlp_forward";
-    if (!X || !Wgate || !Wup || !Wdown || !out || !workspace)
-        return fail(DASS_ERR_NULL, "%s: X, Wgate, Wup, Wdown, out and workspace must not be NULL", fn);
+    const bool eq2_only = Wdown == nullptr;   // y stays in the workspace; out and ldd, ldo are not used
+    if (!X || !Wgate || !Wup || !workspace || (!eq2_only && !out))
+        return fail(DASS_ERR_NULL, "%s: X, Wgate, Wup, workspace (and out, unless Wdown is NULL) must not be NULL", fn);
     if (!valid_dtype(dt))
         return fail(DASS_ERR_DTYPE, "%s: unknown dtype %d", fn, (int)dt);
     if (dt != DASS_BF16)
@@ -1217,19 +1218,19 @@ extern "C" dass_status dass_mlp_forward(const void *X, int64_t T, int64_t ldx, c
     if (d % 64 != 0 || d_int % 64 != 0)
         return fail(DASS_ERR_SHAPE, "%s: d=%lld and d_int=%lld must be multiples of 64", fn, (long long)d,
                     (long long)d_int);
-    if (ldx < d || ldw < d || ldd < d_int || ldo < d)
+    if (ldx < d || ldw < d || (!eq2_only && (ldd < d_int || ldo < d)))
         return fail(DASS_ERR_SHAPE, "%s: a leading dimension is shorter than its row", fn);
-    if (!aligned16(X) || !aligned16(Wgate) || !aligned16(Wup) || !aligned16(Wdown) || !aligned16(out) ||
-        !aligned16(workspace))
+    if (!aligned16(X) || !aligned16(Wgate) || !aligned16(Wup) || !aligned16(workspace) ||
+        (!eq2_only && (!aligned16(Wdown) || !aligned16(out))))
         return fail(DASS_ERR_ALIGN, "%s: every pointer must be 16-byte aligned", fn);
-    if (ldx % 8 != 0 || ldw % 8 != 0 || ldd % 8 != 0 || ldo % 8 != 0)
+    if (ldx % 8 != 0 || ldw % 8 != 0 || (!eq2_only && (ldd % 8 != 0 || ldo % 8 != 0)))
         return fail(DASS_ERR_ALIGN, "%s: leading dimensions must be multiples of 8 elements", fn);
     if (workspace_bytes < dass_mlp_forward_workspace_bytes(T, d, d_int, dt))
         return fail(DASS_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
                     dass_mlp_forward_workspace_bytes(T, d, d_int, dt));
     // 32-bit byte offsets inside a tile's rows, as in dass_calib_norms
     if ((int64_t)P_BM * ldx * 2 >= 0x7fffffffLL || (int64_t)P_BN * ldw * 2 >= 0x7fffffffLL ||
-        (int64_t)P_BM * d_int * 2 >= 0x7fffffffLL || (int64_t)P_BN * ldd * 2 >= 0x7fffffffLL)
+        (int64_t)P_BM * d_int * 2 >= 0x7fffffffLL || (!eq2_only && (int64_t)P_BN * ldd * 2 >= 0x7fffffffLL))
         return fail(DASS_ERR_SHAPE, "%s: rows too long for the tile addressing", fn);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -1250,7 +1251,7 @@ extern "C" dass_status dass_mlp_forward(const void *X, int64_t T, int64_t ldx, c
         if (e != hipSuccess)
             return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
         const dass_status s = check_launch("GLU kernel");
-        if (s != DASS_OK)
+        if (s != DASS_OK || eq2_only)
             return s;
     }
     // Eq. 3: out = y Wdown^T, tiles of 256 tokens x 256 output features, K = d_int

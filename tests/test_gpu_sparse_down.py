@@ -87,6 +87,38 @@ def test_sparse_down_equals_dense_route(gpu_device):
     _check(to_np32(dense), ref, ab, "dense route")
 
 
+def test_eq2_only_then_sparse_down(gpu_device):
+    """dass_mlp_forward without a Down-Proj stops after Eq. 2: the y it leaves in the workspace is
+    bit for bit the y of the full call, and the sparse down projection of it meets the oracle's
+    whole pruned block (bf16 y in between on both sides)."""
+    T, d, d_int = 450, 192, 384
+    g = torch.Generator(device="cpu").manual_seed(21)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(gpu_device)
+    Wg, Wu = ((torch.randn((d_int, d), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device) for _ in range(2))
+    Wd = (torch.randn((d, d_int), generator=g) * 0.1).to(torch.bfloat16).to(gpu_device)
+    norms = torch.rand(d_int, generator=g).to(gpu_device) + 0.5
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    values = torch.empty((d, d_int // 2), dtype=torch.bfloat16, device=gpu_device)
+    meta = torch.empty((d, d_int // 8), dtype=torch.uint8, device=gpu_device)
+    dass.compress_24(Wd, "cols", values, meta)
+    nbytes = dass.mlp_forward_workspace_bytes(T, d, d_int)
+    ws_full = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    ws_eq2 = torch.full((nbytes,), 0x55, dtype=torch.uint8, device=gpu_device)
+    dense = torch.empty((T, d), dtype=torch.bfloat16, device=gpu_device)
+    dass.mlp_forward(X, Wg, Wu, Wd, "gelu_tanh", dense, workspace=ws_full)
+    dass.mlp_forward(X, Wg, Wu, None, "gelu_tanh", None, workspace=ws_eq2)
+    torch.cuda.synchronize()
+    assert torch.equal(ws_full, ws_eq2)
+    sparse = torch.empty_like(dense)
+    dass.down_proj_sparse24(ws_eq2.view(torch.bfloat16).view(T, d_int), values, meta, sparse)
+    torch.cuda.synchronize()
+    ref, ab = oracle.mlp_forward(to_np32(X), to_np32(Wg), to_np32(Wu), to_np32(Wd), "gelu_tanh", want_abs=True)
+    err = np.abs(to_np32(sparse).astype(np.float64) - ref) / (2.0 ** -8 * (np.abs(ref) + 1.5 * ab) + 1e-30)
+    assert float(err.max()) <= 1.0, f"sparse block output at {err.max():.2f} of its tolerance"
+    with pytest.raises(ValueError):
+        dass.mlp_forward(X, Wg, Wu, None, "gelu_tanh", None)
+
+
 def test_sparse_down_full_size(gpu_device):
     """LLaMA2-7B-shaped Down-Proj with DaSS 2:4 weights, 32768 tokens, sampled tokens against the
     oracle (first, last, both sides of tile boundaries, seeded random ones)."""

@@ -156,7 +156,8 @@ def _fwd(lib, X=FAKE, T=256, ldx=128, Wg=FAKE, Wu=FAKE, ldw=128, Wd=FAKE, ldd=19
 
 def test_mlp_forward_rejections(lib):
     assert _fwd(lib, X=None) == "DASS_ERR_NULL"
-    assert _fwd(lib, Wd=None) == "DASS_ERR_NULL"
+    assert _fwd(lib, out=None) == "DASS_ERR_NULL"               # out may be absent only together with Wdown
+    assert _fwd(lib, Wd=None, out=None, ldd=0, ldo=0, wsb=64) == "DASS_ERR_WORKSPACE"   # Eq. 2 alone: still checked
     assert _fwd(lib, ws=None) == "DASS_ERR_NULL"
     assert _fwd(lib, dt=0) == "DASS_ERR_DTYPE"                  # bf16 only
     assert _fwd(lib, act=9) == "DASS_ERR_DTYPE"
