@@ -431,8 +431,9 @@ __global__ __launch_bounds__(kUBlock) void unstructured_rows_kernel(
 //   C     0xFFFF - index (lines are shorter than 65536).
 // The threshold (the n_keep-th largest composite) is found digit by digit, most significant
 // first: 11 + 11 + 10 bits for A and for B, 11 + 5 for C, with one 2048-bin histogram per line
-// and pass.  Almost always the first three passes settle it: the search stops as soon as every
-// candidate left in the chosen bin is wanted.
+// and pass.  The search stops as soon as every candidate left in the chosen bin is wanted, and
+// after two passes (22 bits of A) the candidates left are so few that they are listed and ranked
+// directly; only a line with more than 64 of them goes on with the third pass.
 // ===========================================================================
 constexpr int kLrBins = 2048;
 constexpr int kLrLines = 8;
@@ -717,10 +718,12 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
         }
     };
 
-    // After the three passes on field A a line is still open only when several scores share the
-    // threshold's A.  They are few: each goes into the line's list as (B, C), and one wavefront
-    // ranks them directly (a list that overflows leaves the line to the digit passes on B and C).
-    auto collect_ties = [&]() __attribute__((always_inline)) {
+    // The scores of an open line that agree with the decided digits of A above bit `shift` go
+    // into the line's list as (B, low 10 bits of A : C), and one wavefront ranks them directly.
+    // shift 10, after two passes: the threshold's 22-bit bin, a handful of scores, so the third
+    // counting pass is not needed; shift 0, after three: the scores that share the threshold's
+    // A.  A list that overflows leaves the line to the next counting pass.
+    auto collect_ties = [&](int shift) __attribute__((always_inline)) {
         const uint32_t t = fresh_tid();
         uint32_t sa[kLrLines];
         if constexpr (GATE) {
@@ -747,32 +750,41 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
                     const int line = GATE ? line0 + e : line0;
                     const float w = fabsf(elem_of<DT>(v[j], e));
                     const float p = w * fs[e];
-                    if (__float_as_uint(p) == (GATE ? sa[line] : da)) {
+                    if (((__float_as_uint(p) ^ (GATE ? sa[line] : da)) >> shift) == 0) {
                         const uint32_t slot = atomicAdd(tie_count + line, 1u);
                         if (slot < (uint32_t)kLrTies) {
                             const uint32_t idx = GATE ? vec_pos(j, t) : vec_pos(j, t) * EPV + e;
-                            tie_list[line * kLrTies + slot] = make_uint2(lr_mono(fmaf(w, fs[e], -p)), 0xFFFFu - idx);
+                            tie_list[line * kLrTies + slot] = make_uint2(
+                                lr_mono(fmaf(w, fs[e], -p)), ((__float_as_uint(p) & 0x3ffu) << 16) | (0xFFFFu - idx));
                         }
                     }
                 }
             }
         }
     };
-    // Wavefront `line` ranks its line's list and closes the line on the entry of the wanted rank.
+    // Wavefront `line` ranks its line's list by (A, B, C) and closes the line on the entry of
+    // the wanted rank.  The list holds every score of its bin, so an entry whose A no other
+    // entry shares is a threshold on A alone (fields B and C stay 0: keep iff A >= threshold).
     auto rank_ties = [&](int line) {
         const uint32_t n = tie_count[line];
         if (n > (uint32_t)kLrTies)
             return;
         const uint32_t lane = tid & 63;
         const uint2 mine = tie_list[line * kLrTies + (lane < n ? lane : 0)];
-        uint32_t above = 0;
+        const uint32_t ma = mine.y >> 16, mc = mine.y & 0xFFFFu;
+        uint32_t above = 0, same_a = 0;
         for (uint32_t k = 0; k < n; ++k) {
             const uint2 other = tie_list[line * kLrTies + k];
-            above += (other.x > mine.x) | ((other.x == mine.x) & (other.y > mine.y));
+            const uint32_t oa = other.y >> 16, oc = other.y & 0xFFFFu;
+            above += (oa > ma) | ((oa == ma) & ((other.x > mine.x) | ((other.x == mine.x) & (oc > mc))));
+            same_a += oa == ma;
         }
         if (lane < n && above + 1 == state[line].need) {   // composites differ, so exactly one lane
-            state[line].b = mine.x;
-            state[line].c = mine.y;
+            state[line].a |= ma;   // the undecided bits were 0 (all of them decided: the same bits again)
+            if (same_a > 1) {
+                state[line].b = mine.x;
+                state[line].c = mc;
+            }
             state[line].open = 0;
         }
     };
@@ -883,10 +895,29 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
         __syncthreads();
     };
 
-    // The three passes on field A in the two-term form, then the ties.
+    // Field A in the two-term form: two counting passes (22 bits), then the few scores left in
+    // the threshold's bin are ranked directly.  Only a line whose bin holds more than kLrTies
+    // scores (equal scores in number) takes the third counting pass and a second ranking, of the
+    // scores that share the threshold's A.
     bool open_lines = true;
+    // Ranking of the open lines' lists; leaves open_lines = a line is still open.
+    auto ties_round = [&](int shift) __attribute__((always_inline)) {
+        collect_ties(shift);
+        __syncthreads();
+        const int wave = tid / 64;
+        if (wave < n_lines && state[wave].open)   // uniform inside the wavefront
+            rank_ties(wave);
+        if (tid == 0)
+            flags[0] = 0;
+        __syncthreads();
+        if (tid < n_lines && state[tid].open)
+            flags[0] = 1;
+        __syncthreads();
+        open_lines = flags[0] != 0;
+        __syncthreads();
+    };
     if (!exact) {
-        for (int pass = 0; pass < 3; ++pass) {
+        for (int pass = 0; pass < 2; ++pass) {
             run_pass(pass, std::true_type{});
             if (flags[1]) {   // start again on f64 products (uniform)
                 exact = true;
@@ -899,20 +930,16 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
             __syncthreads();   // flags[0] is cleared at the top of the next pass
         }
         __syncthreads();
-        if (!exact && open_lines) {   // field A is decided and some line has ties on it
-            collect_ties();
-            __syncthreads();
-            const int wave = tid / 64;
-            if (wave < n_lines && state[wave].open)   // uniform inside the wavefront
-                rank_ties(wave);
-            if (tid == 0)
-                flags[0] = 0;
-            __syncthreads();
-            if (tid < n_lines && state[tid].open)
-                flags[0] = 1;
-            __syncthreads();
+        if (!exact && open_lines)
+            ties_round(10);
+        if (!exact && open_lines) {   // a bin with more than kLrTies scores
+            if (tid < kLrLines)
+                tie_count[tid] = 0;   // ordered before the next collection by the barriers of the pass
+            run_pass(2, std::true_type{});
             open_lines = flags[0] != 0;
             __syncthreads();
+            if (open_lines)
+                ties_round(0);
         }
     }
     // What is left (a tie list that overflowed: from field B on; the f64 form: from the start)

@@ -138,6 +138,34 @@ def test_unstructured_scores_equal_to_f32_precision(gpu_device, axes):
         assert bits_equal(Wc, want), first_mismatch(Wc, want)
 
 
+@pytest.mark.parametrize("axes", [("rows", "rows"), ("cols", "cols")])
+@pytest.mark.parametrize("cluster", [48, 300])
+def test_unstructured_threshold_inside_a_cluster_of_close_scores(gpu_device, axes, cluster):
+    """The threshold falls among scores that differ only in the last 10 bits of their f32 form, some
+    of them equal: 48 of them (ranked directly after two digit passes) or 300 (more than the
+    direct ranking holds, so the last digit pass runs too).  Norms are 1: scores are |w|, f32."""
+    length, lines, big = 2048, 16, 900
+    g = torch.Generator(device="cpu").manual_seed(23 + cluster)
+    steps = torch.randint(0, cluster // 2, (lines, cluster), generator=g)       # about 2 weights per value
+    close = (torch.full((lines, cluster), 0x3F800000, dtype=torch.int64) + steps).to(torch.int32).view(torch.float32)
+    large = 2.0 + torch.rand((lines, big), generator=g)
+    small = 0.1 + 0.4 * torch.rand((lines, length - big - cluster), generator=g)
+    W = torch.cat([large, close, small], dim=1)
+    W = W * torch.where(torch.rand(W.shape, generator=g) < 0.5, -1.0, 1.0)
+    W = torch.stack([row[torch.randperm(length, generator=g)] for row in W])   # lines are rows here
+    if axes[1] == "rows":
+        W = W.t().contiguous()
+    W = W.to(gpu_device)
+    nrm = torch.ones(length, device=gpu_device)
+    n_small = length - big - cluster
+    for into in (0, 1, 2, 7, cluster // 2, cluster - 2, cluster - 1):           # pruned members of the cluster
+        Wc = W.clone()
+        want, _ = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), axes[0], axes[1], 1.0, n_small + into)
+        dass.score_mask_unstructured(Wc, nrm, axes[0], axes[1], 1.0, n_small + into)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), (into, first_mismatch(Wc, want))
+
+
 def test_unstructured_leading_dimension(gpu_device):
     _run_case(gpu_device, 100, 104, torch.bfloat16, ("cols", "cols"), 1.0, 52, seed=7, pad=24)
     _run_case(gpu_device, 100, 104, torch.float32, ("rows", "rows"), 0.5, 50, seed=8, pad=12)
