@@ -440,7 +440,7 @@ constexpr int kLrLines = 8;
 constexpr int kLrPasses = 8;
 constexpr int kLrThreads = 1024;
 constexpr int kLrVecs = 16;   // 16-byte vectors held by a thread
-constexpr int kLrTies = 64;   // scores equal in field A around the threshold that are ranked directly, per line
+constexpr int kLrTies = 64;   // scores of the threshold's bin that are listed and ranked directly, per line
 
 struct LrState {
     uint32_t a, b, c;   // decided digits of the threshold, undecided bits 0
