@@ -564,7 +564,7 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     uint32_t *flags = reinterpret_cast<uint32_t *>(state + kLrLines);                 // [0] a line is open, [1] f64 form wanted
     uint32_t *trash = flags + 4;                                                      // [64] counters nobody reads
     uint32_t *tie_count = trash + 64;                                                 // [kLrLines]
-    uint2 *tie_list = reinterpret_cast<uint2 *>(tie_count + kLrLines);                // [kLrLines][kLrTies] fields (B, C)
+    uint2 *tie_list = reinterpret_cast<uint2 *>(tie_count + kLrLines);                // [kLrLines][kLrTies] fields (B, low bits of A : C)
     float *fl = reinterpret_cast<float *>(tie_list + kLrLines * kLrTies);             // scaled factors
 
     const int tid = threadIdx.x;
