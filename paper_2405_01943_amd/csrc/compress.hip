@@ -13,7 +13,7 @@
 namespace dass {
 
 constexpr int kCmpBlock = 256;
-constexpr int kCmpUnits = 4;   // units per thread, a block apart (loads in flight)
+constexpr int kCmpUnits = 4;   // most units per thread, a block apart (loads in flight)
 
 // code of a group from its 4-bit nonzero mask: 16 nibbles in one constant
 constexpr uint64_t code_table()
@@ -65,7 +65,7 @@ __device__ __forceinline__ void add_surplus(long long *surplus_out, int mine)
 }
 
 // ---- groups along the columns.  Unit u of row r: elements 8 u .. 8 u + 7.
-template <int DT>
+template <int DT, int UPT>
 __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
     const void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, void *__restrict__ values,
     int64_t ldv, uint8_t *__restrict__ meta, int64_t ldm, long long *surplus_out, uint32_t blocks_per_row)
@@ -79,11 +79,11 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
     char *V = static_cast<char *>(values) + r * ldv * EB;
     uint8_t *M = meta + r * ldm;
 
-    u32x4 v[kCmpUnits][VPU];
-    int64_t unit[kCmpUnits];
+    u32x4 v[UPT][VPU];
+    int64_t unit[UPT];
 #pragma unroll
-    for (int k = 0; k < kCmpUnits; ++k) {
-        unit[k] = ((int64_t)bx * kCmpUnits + k) * kCmpBlock + threadIdx.x;
+    for (int k = 0; k < UPT; ++k) {
+        unit[k] = ((int64_t)bx * UPT + k) * kCmpBlock + threadIdx.x;
         if (unit[k] < units) {
 #pragma unroll
             for (int h = 0; h < VPU; ++h)
@@ -91,9 +91,9 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
         }
     }
     int surplus = 0;
-    uint32_t outv[kCmpUnits][4], outb[kCmpUnits];
+    uint32_t outv[UPT][4], outb[UPT];
 #pragma unroll
-    for (int k = 0; k < kCmpUnits; ++k) {
+    for (int k = 0; k < UPT; ++k) {
         outv[k][0] = outv[k][1] = outv[k][2] = outv[k][3] = outb[k] = 0;
         if (unit[k] >= units)
             continue;
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
     const bool wide_v = ((reinterpret_cast<uintptr_t>(V)) & 15u) == 0;
     const bool wide_m = ((reinterpret_cast<uintptr_t>(M)) & 3u) == 0;
 #pragma unroll
-    for (int k = 0; k < kCmpUnits; ++k) {
+    for (int k = 0; k < UPT; ++k) {
         const bool have = unit[k] < units;
         if constexpr (DT == DASS_BF16) {
             const uint32_t nx = __shfl_down(outv[k][0], 1, 64), ny = __shfl_down(outv[k][1], 1, 64);
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kCmpBlock) void compress_cols_kernel(
 }
 
 // ---- groups along the rows.  Unit: group g (rows 4 g .. 4 g + 3) of column slot s.
-template <int DT>
+template <int DT, int UPT>
 __global__ __launch_bounds__(kCmpBlock) void compress_rows_kernel(
     const void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, void *__restrict__ values,
     int64_t ldv, uint8_t *__restrict__ meta, int64_t ldm, long long *surplus_out, uint32_t blocks_per_row)
@@ -177,11 +177,11 @@ __global__ __launch_bounds__(kCmpBlock) void compress_rows_kernel(
     char *V = static_cast<char *>(values) + 2 * g * ldv * EB;
     uint8_t *M = meta + g * ldm;
 
-    u32x4 v[kCmpUnits][4];
-    int64_t slot[kCmpUnits];
+    u32x4 v[UPT][4];
+    int64_t slot[UPT];
 #pragma unroll
-    for (int k = 0; k < kCmpUnits; ++k) {
-        slot[k] = ((int64_t)bx * kCmpUnits + k) * kCmpBlock + threadIdx.x;
+    for (int k = 0; k < UPT; ++k) {
+        slot[k] = ((int64_t)bx * UPT + k) * kCmpBlock + threadIdx.x;
         if (slot[k] < slots) {
 #pragma unroll
             for (int a = 0; a < 4; ++a)
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(kCmpBlock) void compress_rows_kernel(
     }
     int surplus = 0;
 #pragma unroll
-    for (int k = 0; k < kCmpUnits; ++k) {
+    for (int k = 0; k < UPT; ++k) {
         if (slot[k] >= slots)
             continue;
         uint32_t lo[EPV], hi[EPV], codes = 0;
@@ -273,24 +273,41 @@ extern "C" dass_status dass_compress_24(const void *W, int64_t rows, int64_t col
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t per_line = along_rows ? cols / vec : cols / 8;      // units of one (group) row
     const int64_t lines = along_rows ? rows / 4 : rows;
-    const int64_t bpr = (per_line + kCmpBlock * kCmpUnits - 1) / (kCmpBlock * kCmpUnits);
+    // Units per thread (4, 2 or 1, a block apart): the count that wastes the fewest lanes on the
+    // ragged last block of a line; more units per thread on a tie (more loads in flight).
+    int upt = kCmpUnits;
+    int64_t bpr = 0;
+    for (int u = kCmpUnits, best = -1; u >= 1; u /= 2) {
+        const int64_t span = (int64_t)kCmpBlock * u, b = (per_line + span - 1) / span;
+        const int fill = (int)(per_line * 1024 / (b * span));
+        if (fill > best) {
+            best = fill;
+            upt = u;
+            bpr = b;
+        }
+    }
     if (bpr * lines > 0x7fffffffLL)
         return fail(DASS_ERR_SHAPE, "%s: too many blocks for one launch; split the rows", fn);
     const dim3 grid((unsigned)(bpr * lines)), block(kCmpBlock);
+    using k_t = void (*)(const void *, int64_t, int64_t, int64_t, void *, int64_t, uint8_t *, int64_t, long long *,
+                         uint32_t);
+    k_t k;
     if (along_rows) {
         if (dt == DASS_BF16)
-            hipLaunchKernelGGL(compress_rows_kernel<DASS_BF16>, grid, block, 0, stream, W, rows, cols, ld, values_out,
-                               ldv, meta_out, ldm, surplus_out, (uint32_t)bpr);
+            k = upt == 4 ? compress_rows_kernel<DASS_BF16, 4> : upt == 2 ? compress_rows_kernel<DASS_BF16, 2>
+                                                                          : compress_rows_kernel<DASS_BF16, 1>;
         else
-            hipLaunchKernelGGL(compress_rows_kernel<DASS_F32>, grid, block, 0, stream, W, rows, cols, ld, values_out,
-                               ldv, meta_out, ldm, surplus_out, (uint32_t)bpr);
+            k = upt == 4 ? compress_rows_kernel<DASS_F32, 4> : upt == 2 ? compress_rows_kernel<DASS_F32, 2>
+                                                                         : compress_rows_kernel<DASS_F32, 1>;
     } else {
         if (dt == DASS_BF16)
-            hipLaunchKernelGGL(compress_cols_kernel<DASS_BF16>, grid, block, 0, stream, W, rows, cols, ld, values_out,
-                               ldv, meta_out, ldm, surplus_out, (uint32_t)bpr);
+            k = upt == 4 ? compress_cols_kernel<DASS_BF16, 4> : upt == 2 ? compress_cols_kernel<DASS_BF16, 2>
+                                                                          : compress_cols_kernel<DASS_BF16, 1>;
         else
-            hipLaunchKernelGGL(compress_cols_kernel<DASS_F32>, grid, block, 0, stream, W, rows, cols, ld, values_out,
-                               ldv, meta_out, ldm, surplus_out, (uint32_t)bpr);
+            k = upt == 4 ? compress_cols_kernel<DASS_F32, 4> : upt == 2 ? compress_cols_kernel<DASS_F32, 2>
+                                                                         : compress_cols_kernel<DASS_F32, 1>;
     }
+    hipLaunchKernelGGL(k, grid, block, 0, stream, W, rows, cols, ld, values_out, ldv, meta_out, ldm, surplus_out,
+                       (uint32_t)bpr);
     return check_launch("compress kernel");
 }
