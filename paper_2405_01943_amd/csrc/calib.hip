@@ -900,7 +900,8 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
             const int row = c / CPR, cc = c % CPR;
             const int64_t t = t0 + row, n = n0 + cc * 8;
             if (t < T && n < d_int)   // d_int is a multiple of 8: a chunk is inside or outside
-                *reinterpret_cast<u32x4 *>(out + t * ldo + n) = *reinterpret_cast<const u32x4 *>(lds64 + row * SROW + cc * 16);
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(lds64 + row * SROW + cc * 16),
+                                            reinterpret_cast<u32x4 *>(out + t * ldo + n));   // streamed: not read again from L2
         }
     }
 }

@@ -286,7 +286,8 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
         const int row = c / CPR, cc = c % CPR;
         const int64_t t = t0 + row, f = f0 + cc * 8;
         if (t < T && f < d)   // d is a multiple of 8: a chunk is inside or outside
-            *reinterpret_cast<u32x4 *>(out + t * ldo + f) = *reinterpret_cast<const u32x4 *>(lds + row * SROW + cc * 16);
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(lds + row * SROW + cc * 16),
+                                        reinterpret_cast<u32x4 *>(out + t * ldo + f));   // streamed: not read again from L2
     }
 }
 
