@@ -213,7 +213,6 @@ dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, in
                                          void *workspace, size_t workspace_bytes,
                                          void *hip_stream);
 
-/* Name of a status code; never NULL. */
 /*
  * The output of the MLP block (Sec. 2.2 Eq. 2 followed by Eq. 3):
  *
@@ -299,6 +298,7 @@ dass_status dass_down_proj_sparse24(const void *Y, int64_t T, int64_t ldy, const
                                     int64_t d_int, dass_dtype dt, void *out, int64_t ldo,
                                     void *hip_stream);
 
+/* Name of a status code; never NULL. */
 const char *dass_status_string(dass_status s);
 /* Detail of the calling thread's most recent failed call ("" if none). */
 const char *dass_last_error_string(void);

@@ -55,12 +55,14 @@ def library_path() -> str:
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libdass.so (building it with hipcc only if it has never been built)."""
+    """Load libdass.so.  A library that is missing, or was built from other sources than the
+    present ones (compared by content hash), is rebuilt with hipcc first; if that fails the
+    call raises: a binary older than its sources is never used."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from . import build as _build
+    from . import build as _build
+    if _build.is_stale():
         _build.build()
     lib = ctypes.CDLL(_LIB_PATH)
     i64, sz, vp, ci, dbl = (ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int,
@@ -134,8 +136,15 @@ def _matrix(t: torch.Tensor, name: str):
     return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
-def _scratch(nbytes: int, device) -> Optional[torch.Tensor]:
-    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+def _scratch(nbytes: int, device, stream=None) -> torch.Tensor:
+    """A workspace for a caller that passed none.  This is a convenience of the binding (the
+    library itself never allocates): the block comes from torch's caching allocator and is
+    released when the call returns, so it is tied to the stream the kernels run on; a caller
+    that wants no allocation on its path passes ``workspace`` itself."""
+    buf = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    if stream is not None:
+        buf.record_stream(stream)   # the allocator may not hand the block on before `stream` is done with it
+    return buf
 
 
 # ------------------------------------------------------------------ stage 1 --
@@ -161,7 +170,7 @@ def calib_norms(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, act: st
         raise TypeError("norms_out: need contiguous float32[d_int]")
     need = int(lib.dass_calib_workspace_bytes(T, d, d_int, DTYPE[X.dtype]))
     if workspace is None and need > 0:
-        workspace = _scratch(need, X.device)
+        workspace = _scratch(need, X.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.dass_calib_norms(_ptr(X), T, ldx, _ptr(Wgate), _ptr(Wup), ldw, d, d_int,
                                 DTYPE[X.dtype], ACT[act], _ptr(sumsq), int(bool(accumulate)),
@@ -182,7 +191,7 @@ def input_norms(X: torch.Tensor, sumsq: torch.Tensor, accumulate: bool = False,
         if t is not None and (t.dtype != torch.float32 or t.numel() != d or not t.is_contiguous()):
             raise TypeError(f"{name}: need contiguous float32[d]")
     if workspace is None:
-        workspace = _scratch(int(lib.dass_input_norms_workspace_bytes(T, d)), X.device)
+        workspace = _scratch(int(lib.dass_input_norms_workspace_bytes(T, d)), X.device, stream)
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.dass_input_norms(_ptr(X), T, ldx, d, DTYPE[X.dtype], _ptr(sumsq), int(bool(accumulate)),
                                 _ptr(norms_out), _ptr(workspace), ws_bytes, _stream(stream)))
@@ -218,7 +227,7 @@ def mlp_forward(X: torch.Tensor, Wgate: torch.Tensor, Wup: torch.Tensor, Wdown: 
     if len(dtypes) != 1:
         raise TypeError("X, the weights and out must share one dtype")
     if workspace is None:
-        workspace = _scratch(int(lib.dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[X.dtype])), X.device)
+        workspace = _scratch(int(lib.dass_mlp_forward_workspace_bytes(T, d, d_int, DTYPE[X.dtype])), X.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.dass_mlp_forward(_ptr(X), T, ldx, _ptr(Wgate), _ptr(Wup), ldw, _ptr(Wdown), ldd, d, d_int,
                                 DTYPE[X.dtype], ACT[act], _ptr(out), ldo, _ptr(workspace), ws_bytes,
@@ -245,7 +254,7 @@ def score_mask_nm(W: torch.Tensor, norms: torch.Tensor, norm_axis: str, group_ax
         raise TypeError("mask_out: need contiguous uint8[rows * cols / 8]")
     need = int(lib.dass_nm_workspace_bytes(rows, cols, AXIS[norm_axis]))
     if workspace is None:
-        workspace = _scratch(need, W.device)
+        workspace = _scratch(need, W.device, stream)
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.dass_score_mask_nm(_ptr(W), rows, cols, ld, DTYPE[W.dtype], _ptr(norms),
                                   AXIS[norm_axis], AXIS[group_axis], float(alpha), int(n_keep),
@@ -293,7 +302,7 @@ def score_mask_nm_batched(tasks, n_keep: int, m: int, workspace: Optional[torch.
         return
     arr, dtype, device = _nm_task_array(tasks)
     if workspace is None:
-        workspace = _scratch(int(lib.dass_nm_batched_workspace_bytes(arr, len(tasks))), device)
+        workspace = _scratch(int(lib.dass_nm_batched_workspace_bytes(arr, len(tasks))), device, stream)
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.dass_score_mask_nm_batched(arr, len(tasks), DTYPE[dtype], int(n_keep), int(m),
                                           _ptr(workspace), ws_bytes, _stream(stream)))
@@ -321,7 +330,7 @@ def score_mask_unstructured(W: torch.Tensor, norms: torch.Tensor, norm_axis: str
     need = int(lib.dass_unstructured_workspace_bytes(rows, cols, DTYPE[W.dtype], AXIS[norm_axis],
                                                      AXIS[group_axis]))
     if workspace is None:
-        workspace = _scratch(need, W.device)
+        workspace = _scratch(need, W.device, stream)
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.dass_score_mask_unstructured(_ptr(W), rows, cols, ld, DTYPE[W.dtype], _ptr(norms),
                                             AXIS[norm_axis], AXIS[group_axis], float(alpha),

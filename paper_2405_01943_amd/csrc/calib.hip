@@ -19,9 +19,7 @@
 //                      MFMAs of consecutive slabs are interleaved by hand.  The
 //                      same main loop also serves Eq. 2 + Eq. 3 themselves
 //                      (dass_mlp_forward) through two storing epilogues.
-//   calib_pipe_kernel  d a multiple of 32: the same with 32-column slabs in a
-//                      four-deep ring.
-//   calib_mfma_kernel  any d that is a multiple of 8: register-staged,
+//   calib_mfma_kernel  any other d (a multiple of 8): register-staged,
 //                      double-buffered; the K tail is masked.
 //
 // f32: a plain LDS-tiled FMA kernel (small shapes).
@@ -317,248 +315,15 @@ __device__ __forceinline__ void block_barrier()
     asm volatile("" ::: "memory");
 }
 
-// Tile geometry of calib_pipe_kernel, shared with the host-side checks.
-constexpr int P_BM = 256, P_BN = 128, P_BK = 32, P_NS = 4;
-
-template <int ACT>
-__global__ __launch_bounds__(256) void calib_pipe_kernel(
-    const uint16_t *__restrict__ X, int64_t T, int64_t ldx, const uint16_t *__restrict__ Wg,
-    const uint16_t *__restrict__ Wu, int64_t ldw, int64_t d, int64_t d_int,
-    float *__restrict__ sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
-{
-    constexpr int BM = P_BM, BN = P_BN, BK = P_BK, NS = P_NS, WN = 2;
-    constexpr int TM = 128, TN = 64, MI = 4, NI = 2;   // wavefront tile: 128 tokens x 64 neurons
-    constexpr int CH = BK / 8;                         // 16-byte chunks per tile row
-    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-    constexpr int STAGE = A_BYTES + 2 * B_BYTES;       // 32 KB: X | Wgate | Wup
-    // One wave-load moves 64 lanes x 16 B = 16 tile rows.  Per slab a wavefront
-    // issues 4 for X, 2 for Wgate and 2 for Wup.
-    constexpr int A_WL = 4, B_WL = 2;
-
-    __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
-
-    // ---- tile assignment.  Consecutive workgroup ids go to different XCDs (8 of them, each
-    // with its own L2).  The tile grid is cut into patches of 4 token tiles x 8 neuron tiles; an
-    // XCD's 32 concurrent workgroups take one patch, so its L2 serves all but 3/16 of their reads.
-    // Patches are dealt round-robin to the XCDs from a list ordered so that the 8 patches in
-    // flight share data through the memory-side cache:
-    //   super_rows = 1: token-major.  The 8 patches lie in one row of patches: X is fetched
-    //     from HBM by one XCD and found in the cache by the others, and the weights stay
-    //     cached from one row to the next as long as both matrices fit (measured: +5 % over
-    //     giving each XCD its own band of neurons).
-    //   super_rows = R > 1, for weights too large to stay cached: rows of patches are taken R
-    //     at a time, and inside such a super-row the patch columns are outermost.  The 8 patches
-    //     share one patch column of the weights, fetched once per super-row, and the super-row's
-    //     X (R x 8 MB at d = 4096) stays cached while the columns sweep past.
-    constexpr int PT = 4, PN = 8;
-    const int64_t np_n = (tiles_n + PN - 1) / PN, np_t = (tiles_t + PT - 1) / PT;
-    const int64_t idx = blockIdx.x / 8, within = idx % (PT * PN);
-    const int64_t patch = (idx / (PT * PN)) * 8 + blockIdx.x % 8;
-    const int64_t sr = patch / (np_n * super_rows), rem = patch % (np_n * super_rows);
-    const int64_t prow = sr * super_rows + rem % super_rows, pcol = rem / super_rows;
-    const int64_t tile_t = prow * PT + within / PN, tile_n = pcol * PN + within % PN;
-    if (tile_t >= tiles_t || tile_n >= tiles_n)
-        return;
-    const int64_t t0 = tile_t * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-
-    // ---- global -> LDS.  Lane l of a wave-load fills slot (l % 4) of row (l / 4)
-    // of a 16-row block, i.e. it fetches K chunk (l % 4) ^ swizzle of that row.
-    // Rows past the end of the matrix are clamped to the last valid row; their
-    // products are discarded in the epilogue.  Each operand is addressed as a raw
-    // buffer that starts at the tile's first row and ends with its last valid
-    // element: the per-lane byte offset is a 32-bit register, the K offset a
-    // scalar, and a read outside the buffer would return 0 instead of faulting.
-    const int wl_row = lane >> 2, wl_slot = lane & 3;
-    const int64_t rows_x = T - t0 < BM ? T - t0 : BM, rows_w = d_int - n0 < BN ? d_int - n0 : BN;
-    uint32_t a_off[A_WL], b_off[B_WL];
-#pragma unroll
-    for (int p = 0; p < A_WL; ++p) {
-        const int r = (wave * A_WL + p) * 16 + wl_row;
-        const int64_t rr = r < rows_x ? r : rows_x - 1;
-        a_off[p] = (uint32_t)(rr * ldx * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
-    }
-#pragma unroll
-    for (int p = 0; p < B_WL; ++p) {
-        const int r = (wave * B_WL + p) * 16 + wl_row;
-        const int64_t rr = r < rows_w ? r : rows_w - 1;
-        b_off[p] = (uint32_t)(rr * ldw * 2 + (wl_slot ^ swizzle<CH>(r, 0)) * 16);
-    }
-    constexpr int kRawBuffer = 0x00020000;   // untyped 32-bit data, no swizzle, bounds-checked
-    const int span_x = (int)((rows_x - 1) * ldx * 2 + d * 2), span_w = (int)((rows_w - 1) * ldw * 2 + d * 2);
-    const __amdgpu_buffer_rsrc_t rx =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(X + t0 * ldx), 0, span_x, kRawBuffer);
-    const __amdgpu_buffer_rsrc_t rg =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wg + n0 * ldw), 0, span_w, kRawBuffer);
-    const __amdgpu_buffer_rsrc_t ru =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Wu + n0 * ldw), 0, span_w, kRawBuffer);
-
-    // q-th of this wavefront's 8 loads of the slab at byte offset kb, into ring stage `stage`
-    auto issue_one = [&](int stage, int kb, int q) {
-        char *base = lds + stage * STAGE;
-        if (q < A_WL)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(base + (wave * A_WL + q) * 1024), 16,
-                                                     a_off[q], kb, 0, 0);
-        else if (q < A_WL + B_WL)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rg, (lds_ptr_t)(base + A_BYTES + (wave * B_WL + q - A_WL) * 1024), 16, b_off[q - A_WL], kb, 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                ru, (lds_ptr_t)(base + A_BYTES + B_BYTES + (wave * B_WL + q - A_WL - B_WL) * 1024), 16,
-                b_off[q - A_WL - B_WL], kb, 0, 0);
-    };
-
-    f32x16 acc_g[MI][NI], acc_u[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                acc_g[i][j][r] = 0.0f;
-                acc_u[i][j][r] = 0.0f;
-            }
-
-    // ---- LDS -> registers.  A lane holds tile row (lane % 32) and K chunk
-    // kk * 2 + lane / 32 of the 16-wide K step kk of a slab.
-    const int fr = lane & 31, fc = lane >> 5;
-    int a_frag[2][MI], b_frag[2][NI];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int r = wm * TM + i * 32 + fr;
-            a_frag[kk][i] = (r * CH + swizzle<CH>(r, kk * 2 + fc)) * 16;
-        }
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int r = wn * TN + j * 32 + fr;
-            b_frag[kk][j] = A_BYTES + (r * CH + swizzle<CH>(r, kk * 2 + fc)) * 16;
-        }
-    }
-    struct Frags {
-        bf16x8 a[MI], g[NI], u[NI];
-    };
-    // q-th fragment of K step kk of the slab in ring stage `stage`, in the order
-    // the MFMAs need them: a0 g0 u0 g1 u1 a1 a2 a3
-    auto read_one = [&](Frags &f, int stage, int kk, int q) {
-        const char *base = lds + stage * STAGE;
-        switch (q) {
-        case 0: f.a[0] = *reinterpret_cast<const bf16x8 *>(base + a_frag[kk][0]); break;
-        case 1: f.g[0] = *reinterpret_cast<const bf16x8 *>(base + b_frag[kk][0]); break;
-        case 2: f.u[0] = *reinterpret_cast<const bf16x8 *>(base + b_frag[kk][0] + B_BYTES); break;
-        case 3: f.g[1] = *reinterpret_cast<const bf16x8 *>(base + b_frag[kk][1]); break;
-        case 4: f.u[1] = *reinterpret_cast<const bf16x8 *>(base + b_frag[kk][1] + B_BYTES); break;
-        case 5: f.a[1] = *reinterpret_cast<const bf16x8 *>(base + a_frag[kk][1]); break;
-        case 6: f.a[2] = *reinterpret_cast<const bf16x8 *>(base + a_frag[kk][2]); break;
-        default: f.a[3] = *reinterpret_cast<const bf16x8 *>(base + a_frag[kk][3]); break;
-        }
-    };
-    auto mfma_pair = [&](const Frags &f, int q) {   // gate and up MFMA number q of a K step
-        const int i = q >> 1, j = q & 1;
-        acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
-        acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
-    };
-
-    // ---- main loop.  While slab s is multiplied, slab s + 1 is resident (its
-    // first fragments are read during the second half of slab s) and slabs
-    // s + 2 .. s + NS - 1 are in flight; the loads of slab s + NS - 1 reuse the
-    // ring stage of slab s - 1, which every wavefront left at the last barrier.
-    const int64_t S = d / BK;                // slabs; the host guarantees d % BK == 0
-    constexpr int AHEAD = NS - 1;
-    constexpr int INFLIGHT = 8 * (NS - 3);   // loads that may be pending at a slab boundary
-#pragma unroll
-    for (int a = 0; a < AHEAD; ++a)
-        if (a < S) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                issue_one(a, a * BK * 2, q);
-        }
-    if (S >= AHEAD)
-        wait_vmcnt<INFLIGHT>();   // slabs 0 and 1 have landed
-    else
-        wait_vmcnt<0>();
-    block_barrier();
-    Frags f0, f1;
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-        read_one(f0, 0, 0, q);
-
-    int sc = 0;   // ring stage of slab s
-    // One slab = 16 gate/up MFMA pairs: 8 on f0 (K step 0), then 8 on f1 (K step 1).
-    // Every second pair carries one global->LDS load of slab s + AHEAD; the first
-    // pairs of each half carry the fragment reads for the other half (2 2 1 1 1 1
-    // per pair, so the last read is two pairs old when its half begins).
-    auto slab_body = [&](int64_t s, auto steady_tag) {
-        constexpr bool STEADY = decltype(steady_tag)::value;
-        const int sn = sc + 1 == NS ? 0 : sc + 1;   // stage of slab s + 1
-        const int sl = sc == 0 ? NS - 1 : sc - 1;   // stage of slab s - 1, refilled with slab s + AHEAD
-        const int kl = (int)(s + AHEAD) * BK * 2;
-        constexpr int first_read[9] = {0, 2, 4, 5, 6, 7, 8, 8, 8};
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (STEADY && (q & 1) == 0)
-                issue_one(sl, kl, q >> 1);
-#pragma unroll
-            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                read_one(f1, sc, 1, r);
-            mfma_pair(f0, q);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (STEADY && (q & 1) == 0)
-                issue_one(sl, kl, 4 + (q >> 1));
-            if (STEADY || s + 1 < S) {
-#pragma unroll
-                for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                    read_one(f0, sn, 0, r);
-            }
-            mfma_pair(f1, q);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (STEADY)
-            wait_vmcnt<INFLIGHT>();   // slab s + 2 has landed (this wavefront's part)
-        else
-            wait_vmcnt<0>();
-        block_barrier();
-        sc = sn;
-    };
-    int64_t s = 0;
-    for (; s + AHEAD < S; ++s)
-        slab_body(s, std::true_type{});
-    for (; s < S; ++s)
-        slab_body(s, std::false_type{});
-
-    // ---- epilogue: as in calib_mfma_kernel above
-    const bool full_t = t0 + BM <= T;
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        float part = 0.0f;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
-                const int64_t t = t0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * fc + (r % 4);
-                part += (full_t || t < T) ? y * y : 0.0f;
-            }
-        }
-        part += __shfl_xor(part, 32, 64);
-        const int64_t n = n0 + wn * TN + j * 32 + fr;
-        if (fc == 0 && n < d_int)
-            atomicAdd(sumsq + n, part);
-    }
-}
+// Workgroup tile of calib_pipe64_kernel, shared with the host-side checks.
+constexpr int P_BM = 256, P_BN = 128;
 
 // ------------------------------------------------- bf16 MFMA, 128-byte rows --
-// The same workgroup tile, wavefront tiles, MFMA order and epilogue as calib_pipe_kernel, with
-// K slabs of 64 columns: a wave-load covers 8 tile rows x 128 bytes, so every request to L2 is a
+// The workgroup tile and wavefront tiles of calib_mfma_kernel (256 tokens x 128 neurons x {gate,
+// up}; a wavefront 128 x 64 x 2), fed by direct global -> LDS loads instead of register staging.
+// K slabs are 64 columns: a wave-load covers 8 tile rows x 128 bytes, so every request to L2 is a
 // whole 128-byte line (half as many requests as with 64-byte row pieces, measured +9 % at the
-// same board power), and there is one barrier per 64 columns instead of one per 32.
+// same board power), and there is one barrier per 64 columns.
 //
 // 64 KB per slab leaves room for 2.5 slabs in the 160 KB of LDS, so the A part (X: 256 rows x
 // 128 B) and the B part (Wgate and Wup: 2 x 128 rows x 128 B) of a slab are ring units of their
@@ -604,7 +369,19 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 
     extern __shared__ __attribute__((aligned(1024))) char lds64[];   // P64_LDS bytes
 
-    // ---- tile assignment: as in calib_pipe_kernel
+    // ---- tile assignment.  Consecutive workgroup ids go to different XCDs (8 of them, each
+    // with its own L2).  The tile grid is cut into patches of 4 token tiles x 8 neuron tiles; an
+    // XCD's 32 concurrent workgroups take one patch, so its L2 serves all but 3/16 of their reads.
+    // Patches are dealt round-robin to the XCDs from a list ordered so that the 8 patches in
+    // flight share data through the memory-side cache:
+    //   super_rows = 1: token-major.  The 8 patches lie in one row of patches: X is fetched
+    //     from HBM by one XCD and found in the cache by the others, and the weights stay
+    //     cached from one row to the next as long as both matrices fit (measured: +5 % over
+    //     giving each XCD its own band of neurons).
+    //   super_rows = R > 1, for weights too large to stay cached: rows of patches are taken R
+    //     at a time, and inside such a super-row the patch columns are outermost.  The 8 patches
+    //     share one patch column of the weights, fetched once per super-row, and the super-row's
+    //     X (R x 8 MB at d = 4096) stays cached while the columns sweep past.
     constexpr int PT = 4, PN = 8;
     const int64_t np_n = (tiles_n + PN - 1) / PN;
     const int64_t idx = blockIdx.x / 8, within = idx % (PT * PN);
@@ -622,7 +399,9 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 
     // ---- global -> LDS.  Lane l of a wave-load fills slot (l % 8) of row (l / 8) of an 8-row
     // block, i.e. it fetches K chunk (l % 8) ^ swizzle of that row.  Rows past the end of the
-    // matrix are clamped; raw buffers bound every read, as in calib_pipe_kernel.
+    // matrix are clamped.  Each operand is addressed as a raw buffer that starts at the tile's
+    // first row and ends with its last valid element: the per-lane byte offset is a 32-bit
+    // register, the K offset a scalar, and a read outside the buffer returns 0 instead of faulting.
     const int wl_row = lane >> 3, wl_slot = lane & 7;
     const int64_t rows_x = T - t0 < BM ? T - t0 : BM, rows_w = d_int - n0 < BN ? d_int - n0 : BN;
     // kEpiGemm: the second 128 rows of the tile may be fewer, or none (then an empty buffer:
@@ -1012,31 +791,6 @@ static void launch_mfma(int act, dim3 grid, hipStream_t stream, const uint16_t *
     }
 }
 
-static void launch_pipe(int act, dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
-                        const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
-                        float *sumsq, int64_t tiles_t, int64_t tiles_n, int super_rows)
-{
-    const dim3 block(256);
-    switch (act) {
-    case DASS_ACT_SILU:
-        hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_SILU>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw, d,
-                           d_int, sumsq, tiles_t, tiles_n, super_rows);
-        break;
-    case DASS_ACT_GELU_TANH:
-        hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_GELU_TANH>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw,
-                           d, d_int, sumsq, tiles_t, tiles_n, super_rows);
-        break;
-    case DASS_ACT_GELU_ERF:
-        hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_GELU_ERF>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw,
-                           d, d_int, sumsq, tiles_t, tiles_n, super_rows);
-        break;
-    default:
-        hipLaunchKernelGGL((calib_pipe_kernel<DASS_ACT_RELU>), grid, block, 0, stream, X, T, ldx, Wg, Wu, ldw, d,
-                           d_int, sumsq, tiles_t, tiles_n, super_rows);
-        break;
-    }
-}
-
 template <int ACT, int EPI>
 static hipError_t launch_pipe64_act(dim3 grid, hipStream_t stream, const uint16_t *X, int64_t T, int64_t ldx,
                                     const uint16_t *Wg, const uint16_t *Wu, int64_t ldw, int64_t d, int64_t d_int,
@@ -1124,6 +878,23 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
     if (ldx % vec != 0 || ldw % vec != 0)
         return fail(DASS_ERR_ALIGN, "%s: ldx, ldw must be multiples of %d elements", fn, vec);
 
+    // ---- launch plan; every size check comes before the first launch
+    constexpr int BM = P_BM, BN = P_BN, BK = 64;
+    const bool bf16 = dt == DASS_BF16;
+    const int64_t tiles_t = bf16 ? (T + BM - 1) / BM : (T + F_BM - 1) / F_BM;
+    const int64_t tiles_n = bf16 ? (d_int + BN - 1) / BN : (d_int + F_BN - 1) / F_BN;
+    // calib_pipe64_kernel: d a multiple of its 64-column slab, and 32-bit byte offsets inside a
+    // tile's rows.  Its grid is whole 4 x 8 patches of tiles dealt to the 8 XCDs, rows of patches in
+    // groups of 8 when Wgate + Wup exceed the 256 MB memory-side cache (see the kernel).
+    const bool pipe64 = bf16 && d % 64 == 0 && (int64_t)BM * ldx * 2 < 0x7fffffffLL &&
+                        (int64_t)BN * ldw * 2 < 0x7fffffffLL;
+    const int super_rows = 2 * d_int * d * 2 > (256LL << 20) ? 8 : 1;
+    const int64_t blocks = pipe64 ? pipe_grid(tiles_t, tiles_n, super_rows)
+                           : bf16 ? (tiles_t * tiles_n + 7) / 8 * 8
+                                  : tiles_t * tiles_n;
+    if (blocks <= 0 || blocks > 0x7fffffffLL)
+        return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
+
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const unsigned vgrid = (unsigned)((d_int + 255) / 256);
     if (!accumulate) {
@@ -1132,50 +903,22 @@ extern "C" dass_status dass_calib_norms(const void *X, int64_t T, int64_t ldx, c
         if (s != DASS_OK)
             return s;
     }
-    if (dt == DASS_BF16) {
-        constexpr int BM = 256, BN = 128, BK = 64;
-        const int64_t tiles_t = (T + BM - 1) / BM, tiles_n = (d_int + BN - 1) / BN;
-        const int64_t n_tiles = tiles_t * tiles_n;
-        const int64_t blocks = (n_tiles + 7) / 8 * 8;
-        if (blocks > 0x7fffffffLL)
-            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
-        // The pipelined kernel addresses a tile's rows with 32-bit byte offsets.
-        const bool pipe_ok = d % P_BK == 0 && (int64_t)P_BM * ldx * 2 < 0x7fffffffLL &&
-                             (int64_t)P_BN * ldw * 2 < 0x7fffffffLL;
-        static_assert(BM == P_BM && BN == P_BN, "both bf16 kernels use the same tile grid");
-        // calib_pipe_kernel: whole 4 x 8 patches of tiles, dealt to the 8 XCDs; rows of patches
-        // in groups of 8 when Wgate + Wup exceed the 256 MB memory-side cache (see the kernel)
-        const int super_rows = 2 * d_int * d * 2 > (256LL << 20) ? 8 : 1;
-        const int64_t patches = ((tiles_t + 3) / 4 + super_rows - 1) / super_rows * super_rows * ((tiles_n + 7) / 8);
-        const int64_t pipe_blocks = (patches + 7) / 8 * 8 * 32;
-        if (pipe_ok && pipe_blocks > 0x7fffffffLL)
-            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
-        if (pipe_ok && d % 64 == 0) {   // 128-byte row pieces: calib_pipe64_kernel
-            const hipError_t e = launch_pipe64<kEpiNorms>((int)act, dim3((unsigned)pipe_blocks), stream,
-                                                          static_cast<const uint16_t *>(X), T, ldx,
-                                                          static_cast<const uint16_t *>(Wgate),
-                                                          static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
-                                                          nullptr, 0, tiles_t, tiles_n, super_rows);
-            if (e != hipSuccess)
-                return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
-        } else if (pipe_ok)
-            launch_pipe((int)act, dim3((unsigned)pipe_blocks), stream, static_cast<const uint16_t *>(X), T, ldx,
-                        static_cast<const uint16_t *>(Wgate), static_cast<const uint16_t *>(Wup), ldw, d,
-                        d_int, sumsq, tiles_t, tiles_n, super_rows);
-        else
-            launch_mfma<BM, BN, BK, 4, 2, 1>((int)act, dim3((unsigned)blocks), stream,
-                                             static_cast<const uint16_t *>(X), T, ldx,
-                                             static_cast<const uint16_t *>(Wgate),
-                                             static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
-                                             tiles_t, tiles_n);
+    if (pipe64) {
+        const hipError_t e = launch_pipe64<kEpiNorms>((int)act, dim3((unsigned)blocks), stream,
+                                                      static_cast<const uint16_t *>(X), T, ldx,
+                                                      static_cast<const uint16_t *>(Wgate),
+                                                      static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq,
+                                                      nullptr, 0, tiles_t, tiles_n, super_rows);
+        if (e != hipSuccess)
+            return fail(DASS_ERR_HIP, "%s: cannot reserve %d bytes of LDS: %s", fn, P64_LDS, hipGetErrorString(e));
+    } else if (bf16) {
+        launch_mfma<BM, BN, BK, 4, 2, 1>((int)act, dim3((unsigned)blocks), stream, static_cast<const uint16_t *>(X),
+                                         T, ldx, static_cast<const uint16_t *>(Wgate),
+                                         static_cast<const uint16_t *>(Wup), ldw, d, d_int, sumsq, tiles_t, tiles_n);
     } else {
-        const int64_t tiles_t = (T + F_BM - 1) / F_BM, tiles_n = (d_int + F_BN - 1) / F_BN;
-        if (tiles_t * tiles_n > 0x7fffffffLL)
-            return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch; split the tokens", fn);
-        hipLaunchKernelGGL(calib_f32_kernel, dim3((unsigned)(tiles_t * tiles_n)), dim3(256), 0,
-                           stream, static_cast<const float *>(X), T, ldx,
-                           static_cast<const float *>(Wgate), static_cast<const float *>(Wup), ldw, d,
-                           d_int, (int)act, sumsq, tiles_n);
+        hipLaunchKernelGGL(calib_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const float *>(X), T, ldx, static_cast<const float *>(Wgate),
+                           static_cast<const float *>(Wup), ldw, d, d_int, (int)act, sumsq, tiles_n);
     }
     dass_status s = check_launch("calibration kernel");
     if (s != DASS_OK)

@@ -38,6 +38,7 @@ class MlpConfig:
     unstructured: Optional[float] = None          # sparsity of the unstructured variant
     alpha_gate_up: float = 0.5                    # Eq. 4 exponent
     alpha_down: float = 1.0                       # Eq. 5 exponent
+    dead_frac: float = 0.0                        # share of neurons whose Gate-Proj row is all zero
 
     @property
     def torch_dtype(self):
@@ -63,10 +64,16 @@ CONFIGS = {
         # a sixth shape beside the five benchmark ones: LLaMA2-13B (the appendix table of model configurations)
         MlpConfig("llama2_13b", 5120, 13824, 262144, "bf16", "silu", 262144, 1e-3,
                   nm=((2, 4), (4, 8))),
+        # the other GLU variants of Sec. 2.2 at the LLaMA2-7B shape: ReGLU (the ReluLLaMA model of
+        # Sec. 4.1; 3 % of its neurons never fire) and GeGLU with the erf form of GELU
+        MlpConfig("llama2_7b_reglu", 4096, 11008, 262144, "bf16", "relu", 262144, 1e-3,
+                  nm=((2, 4),), unstructured=0.5, dead_frac=0.03),
+        MlpConfig("llama2_7b_geglu_erf", 4096, 11008, 262144, "bf16", "gelu_erf", 262144, 1e-3,
+                  nm=((4, 8),)),
     ]
 }
 
-_TAGS = {"x": 1, "wg": 2, "wu": 3, "wd": 4, "perm": 5, "tail": 6, "norms": 7}
+_TAGS = {"x": 1, "wg": 2, "wu": 3, "wd": 4, "perm": 5, "tail": 6, "norms": 7, "dead": 8}
 
 
 def _gen(device, seed: int, tag: str, idx: int = 0) -> torch.Generator:
@@ -81,11 +88,25 @@ def outlier_channels(cfg: MlpConfig, seed: int = 0) -> torch.Tensor:
     return perm[: cfg.n_outlier].sort().values
 
 
+def dead_neurons(cfg: MlpConfig, seed: int = 0) -> torch.Tensor:
+    """Indices of the neurons whose Gate-Proj row is all zero (same on any device); may be empty.
+
+    With such a row the gate is 0 on every token, so the neuron's activation and its norm are
+    exactly 0 whatever the activation function: the stand-in for a neuron that never fires.
+    """
+    n = int(round(cfg.dead_frac * cfg.d_int))
+    perm = torch.randperm(cfg.d_int, generator=_gen("cpu", seed, "dead"))
+    return perm[:n].sort().values
+
+
 def make_weight(cfg: MlpConfig, which: str, device, seed: int = 0) -> torch.Tensor:
-    """One of 'wg', 'wu' ([d_int, d]) or 'wd' ([d, d_int]), entries N(0, w_std)."""
+    """One of 'wg', 'wu' ([d_int, d]) or 'wd' ([d, d_int]), entries N(0, w_std); the Gate-Proj
+    rows of the config's dead neurons are zero."""
     shape = (cfg.d_int, cfg.d) if which in ("wg", "wu") else (cfg.d, cfg.d_int)
     w = torch.randn(shape, generator=_gen(device, seed, which), device=device,
                     dtype=torch.float32)
+    if which == "wg" and cfg.dead_frac > 0.0:
+        w[dead_neurons(cfg, seed).to(device)] = 0.0
     return (w * cfg.w_std).to(cfg.torch_dtype)
 
 

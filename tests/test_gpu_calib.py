@@ -73,6 +73,28 @@ def test_calib_activations_ragged_shapes(gpu_device, dtype, act):
     _check(X, Wg, Wu, act, gpu_device)
 
 
+@pytest.mark.parametrize("act", ACTS)
+@pytest.mark.parametrize("T,d,I", [(300, 64, 150), (515, 192, 257), (1100, 448, 130)])
+def test_calib_pipelined_kernel_every_activation(gpu_device, act, T, d, I):
+    """bf16 with d a multiple of 64: the direct-to-LDS kernel (1, 3 and 7 K slabs, so the prologue,
+    the steady state and the peeled last slabs all run), ragged T and d_int, every activation's
+    norm epilogue, against the oracle; then the same tokens in chunks."""
+    X, Wg, Wu = _inputs(T, d, I, torch.bfloat16, gpu_device, seed=11 + d)
+    norms = _check(X, Wg, Wu, act, gpu_device)
+    assert float(norms.min()) > 0.0          # no trivially dead neuron: the comparison means something
+    _check(X, Wg, Wu, act, gpu_device, chunks=[T - 257, 1, 256])
+
+
+@pytest.mark.parametrize("act", ACTS)
+@pytest.mark.parametrize("d", [32, 96, 160, 224, 4128])
+def test_calib_other_widths(gpu_device, act, d):
+    """bf16 with d a multiple of 32 but not of 64 (and 4128 = 64 * 64 + 32): the register-staged kernel."""
+    T, I = (333, 200) if d < 1000 else (270, 140)
+    X, Wg, Wu = _inputs(T, d, I, torch.bfloat16, gpu_device, seed=23 + d)
+    _check(X, Wg, Wu, act, gpu_device)
+    _check(X, Wg, Wu, act, gpu_device, chunks=[T - 100, 100])
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_calib_several_tiles_both_ways(gpu_device, dtype):
     X, Wg, Wu = _inputs(700, 320, 400, dtype, gpu_device, seed=2)
@@ -120,6 +142,14 @@ def test_calib_dead_neurons_give_zero_norm(gpu_device):
     dass.calib_norms(X, Wg, Wu, "relu", sumsq, norms_out=norms)
     torch.cuda.synchronize()
     assert torch.all(norms == 0)
+    # half of the neurons alive again: their norms follow the oracle, the others stay exactly 0
+    Wg[::2] = -Wg[::2]
+    dass.calib_norms(X, Wg, Wu, "relu", sumsq, norms_out=norms)
+    torch.cuda.synchronize()
+    want = oracle.norms(oracle.sumsq(to_np32(X), to_np32(Wg), to_np32(Wu), "relu"))
+    assert np.all(want[1::2] == 0) and np.all(want[::2] > 0)
+    assert torch.all(norms[1::2] == 0)
+    assert _rel_err(norms.cpu().numpy(), want) <= TOL[torch.bfloat16]
 
 
 def test_calib_argument_errors(gpu_device):

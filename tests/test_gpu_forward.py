@@ -4,11 +4,13 @@ Tolerance, derived from the arithmetic.  bf16 keeps 8 significant bits: rounding
 relative error at most u = 2^-8.  With A = sum_i |y_i Wdown[j, i]| from the oracle:
   - y is rounded to bf16 once: every term of the Eq. 3 sum moves by at most u of itself, the sum
     by at most u A;
-  - the f32 evaluation of y and the f32 accumulation of the sum add at most (eps + K 2^-24) A,
-    K = d_int <= 28672, i.e. less than 0.5 u A even by the worst-case linear bound;
+  - the f32 evaluation of y and the f32 accumulation of the K = d_int <= 28672 terms: rounding
+    errors of 2^-24 relative that add like a random walk, about sqrt(K) 2^-24 A = 1e-5 A = 0.003 u A;
+    0.05 u A leaves that a factor of 16 (the worst-case linear bound K 2^-24 A = 0.44 u A is never
+    approached: it needs every one of 28672 roundings to go the same way);
   - the output is rounded to bf16 once: at most u of its value.
-Hence |gpu - oracle| <= u |oracle| + 1.5 u A (second-order terms fall inside the slack of the
-last factor).
+Hence |gpu - oracle| <= u |oracle| + 1.05 u A.  The first two terms are exact worst cases, so the
+bound cannot be much tighter; observed: the worst element at 0.36 of it, the mean below 0.1.
 """
 import numpy as np
 import pytest
@@ -25,7 +27,7 @@ pytestmark = pytest.mark.gpu
 
 def _check(out, ref, ab, what):
     out = np.asarray(out, dtype=np.float64)
-    tol = 2.0 ** -8 * (np.abs(ref) + 1.5 * ab) + 1e-30
+    tol = 2.0 ** -8 * (np.abs(ref) + 1.05 * ab) + 1e-30
     err = np.abs(out - ref)
     worst = float(np.max(err / tol))
     assert worst <= 1.0, f"{what}: worst error / tolerance = {worst:.3f}"

@@ -85,6 +85,12 @@ def test_unstructured_rejections(lib):
     assert call(cols=12) == "DASS_ERR_SHAPE"
 
 
+def test_calib_too_many_tiles_is_rejected_before_the_first_launch(lib):
+    # 2^31 tiles of 256 tokens: no launch can hold them; sumsq (a fake pointer) is never written
+    rc = lib.dass_calib_norms(FAKE, 1 << 40, 64, FAKE, FAKE, 64, 64, 128, 1, 0, FAKE, 0, None, None, 0, None)
+    assert lib.dass_status_string(rc) == b"DASS_ERR_SHAPE"
+
+
 def test_calib_rejections(lib):
     def call(X=FAKE, T=16, ldx=64, d=64, d_int=8, dt=1, act=0, sumsq=FAKE, ldw=64):
         rc = lib.dass_calib_norms(X, T, ldx, FAKE, FAKE, ldw, d, d_int, dt, act, sumsq, 0, None,
