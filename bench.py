@@ -16,6 +16,11 @@ through the caches, so the weights come from HBM).  `stage2.cold_*` repeats one
 launch at a time on copies that rotate through more memory than the 256 MB
 last-level cache.  `cpu_baseline` times the float64 oracle on this machine's
 host cores on a bounded sample.
+
+Beside the headline the same line carries the rest of the report: `roofline_stage2_48` (the
+workload's matrices at 4:8, in a step and launch by launch), `stage2_other_reading` (Gate-Proj
+with the groups along the input dimension), `unstructured` (50 % per comparison group, per
+matrix), and `all_configs` (stage 1 and stage 2 of every other configuration, a few steps each).
 """
 from __future__ import annotations
 
@@ -67,7 +72,98 @@ def parse_args():
     ap.add_argument("--model-layers", type=int, default=32,
                     help="layers of the whole-model stage-2 measurement (0 skips it)")
     ap.add_argument("--stage2-launches", type=int, default=24)
+    ap.add_argument("--other-configs", default="all",
+                    help="'all', 'none' or a comma-separated list: configurations reported under all_configs")
+    ap.add_argument("--other-steps", type=int, default=3)
     return ap.parse_args()
+
+
+def make_inputs(cfg, dev):
+    """X, Wgate, Wup, Wdown of a configuration, generated on the device chunk by chunk."""
+    import torch
+
+    from paper_2405_01943_amd import synth
+
+    T = cfg.tokens
+    gen_chunk = min(T, 32768)
+    X = torch.empty((T, cfg.d), dtype=cfg.torch_dtype, device=dev)
+    for c in range((T + gen_chunk - 1) // gen_chunk):
+        lo = c * gen_chunk
+        n = min(gen_chunk, T - lo)
+        X[lo:lo + n] = synth.make_x(cfg, c, n, dev)
+    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
+    return X, Wg, Wu, Wd
+
+
+def run_steps(cfg, n_keep, m, X, Wg, Wu, Wd, steps, warmup):
+    """`warmup` untimed and `steps` timed passes of the hot path (calibration norms over all tokens,
+    then the three N:M masks on fresh copies).  Returns (wall ms per step, stage-1 ms, stage-2 ms, norms);
+    the stage times are means of HIP-event intervals on the launch stream."""
+    import torch
+
+    import paper_2405_01943_amd as dass
+
+    dev = X.device
+    T, d, I = cfg.tokens, cfg.d, cfg.d_int
+    Wg_p, Wu_p, Wd_p = (torch.empty_like(w) for w in (Wg, Wu, Wd))
+    sumsq = torch.empty(I, device=dev)
+    norms = torch.empty(I, device=dev)
+    ws_gate = torch.empty(max(16, dass.nm_workspace_bytes(I, d, "rows")), dtype=torch.uint8, device=dev)
+    ws_down = torch.empty(max(16, dass.nm_workspace_bytes(d, I, "cols")), dtype=torch.uint8, device=dev)
+    chunks = [(lo, min(cfg.chunk, T - lo)) for lo in range(0, T, cfg.chunk)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+
+    def step():
+        Wg_p.copy_(Wg); Wu_p.copy_(Wu); Wd_p.copy_(Wd)
+        e = [ev() for _ in range(3)]
+        e[0].record()
+        for k, (lo, n) in enumerate(chunks):
+            dass.calib_norms(X[lo:lo + n], Wg, Wu, cfg.act, sumsq, accumulate=k > 0,
+                             norms_out=norms if k == len(chunks) - 1 else None)
+        e[1].record()
+        dass.score_mask_nm(Wg_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
+        dass.score_mask_nm(Wu_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
+        dass.score_mask_nm(Wd_p, norms, "cols", "cols", cfg.alpha_down, n_keep, m, workspace=ws_down)
+        e[2].record()
+        return e
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = [step() for _ in range(steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    s1 = sum(e[0].elapsed_time(e[1]) for e in evs) / steps
+    s2 = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
+    return wall * 1e3 / steps, s1, s2, norms
+
+
+def cold_launch_us(W0, launch, n_launches, n_copies):
+    """One launch at a time on copies of W0 that rotate through more memory than the 256 MB
+    last-level cache; every copy is restored and the others are touched before it is timed.
+    `launch(w)` enqueues the call under test on w.  Returns median and minimum in microseconds."""
+    import torch
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    copies = [W0.clone() for _ in range(n_copies)]
+    times = []
+    for it in range(n_launches + 4):
+        w = copies[it % n_copies]
+        w.copy_(W0)
+        for other in copies:
+            if other is not w:
+                other.add_(0)
+        a, b = ev(), ev()
+        a.record()
+        launch(w)
+        b.record()
+        torch.cuda.synchronize()
+        if it >= 4:
+            times.append(a.elapsed_time(b))
+    del copies
+    return {"median_us": statistics.median(times) * 1e3, "min_us": min(times) * 1e3}
 
 
 def cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X_sample, norms32):
@@ -127,82 +223,67 @@ def main():
     esz = 2 if cfg.dtype == "bf16" else 4
 
     # ---- synthetic inputs, generated on the device chunk by chunk ----------------------
-    gen_chunk = min(T, 32768)
-    X = torch.empty((T, d), dtype=cfg.torch_dtype, device=dev)
-    for c in range((T + gen_chunk - 1) // gen_chunk):
-        lo = c * gen_chunk
-        n = min(gen_chunk, T - lo)
-        X[lo:lo + n] = synth.make_x(cfg, c, n, dev)
-    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
-    Wg_p, Wu_p, Wd_p = (torch.empty_like(w) for w in (Wg, Wu, Wd))
-    sumsq = torch.empty(I, device=dev)
-    norms = torch.empty(I, device=dev)
-    ws_gate = torch.empty(dass.nm_workspace_bytes(I, d, "rows"), dtype=torch.uint8, device=dev)
-    ws_down = torch.empty(dass.nm_workspace_bytes(d, I, "cols"), dtype=torch.uint8, device=dev)
-    chunks = [(lo, min(cfg.chunk, T - lo)) for lo in range(0, T, cfg.chunk)]
-    torch.cuda.synchronize()
-
+    X, Wg, Wu, Wd = make_inputs(cfg, dev)
+    ws_gate = torch.empty(max(16, dass.nm_workspace_bytes(I, d, "rows")), dtype=torch.uint8, device=dev)
+    ws_down = torch.empty(max(16, dass.nm_workspace_bytes(d, I, "cols")), dtype=torch.uint8, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    s1_ms, s2_ms = [], []
 
-    def step(record: bool):
-        Wg_p.copy_(Wg); Wu_p.copy_(Wu); Wd_p.copy_(Wd)
-        e = [ev() for _ in range(3)]
-        e[0].record()
-        for k, (lo, n) in enumerate(chunks):
-            dass.calib_norms(X[lo:lo + n], Wg, Wu, cfg.act, sumsq, accumulate=k > 0,
-                             norms_out=norms if k == len(chunks) - 1 else None)
-        e[1].record()
-        dass.score_mask_nm(Wg_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
-        dass.score_mask_nm(Wu_p, norms, "rows", "rows", cfg.alpha_gate_up, n_keep, m, workspace=ws_gate)
-        dass.score_mask_nm(Wd_p, norms, "cols", "cols", cfg.alpha_down, n_keep, m, workspace=ws_down)
-        e[2].record()
-        if record:
-            return e
-        return None
-
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    evs = [step(True) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    for e in evs:
-        s1_ms.append(e[0].elapsed_time(e[1]))
-        s2_ms.append(e[1].elapsed_time(e[2]))
-    ms_per_step = wall * 1e3 / args.steps
-    s1_avg = sum(s1_ms) / len(s1_ms)
-    s2_avg = sum(s2_ms) / len(s2_ms)
+    # ---- the timed steps -------------------------------------------------------------------
+    ms_per_step, s1_avg, s2_avg, norms = run_steps(cfg, n_keep, m, X, Wg, Wu, Wd, args.steps, args.warmup)
     flops = 4.0 * T * d * I
     s1_tflops = flops / (s1_avg * 1e-3) / 1e12
 
     # ---- stage 2, launch by launch, on copies rotating through > 256 MB ------------------
     n_copies = max(2, int(320e6 // (Wd.numel() * esz)) + 1)
-    cold = {}
-    for name, W0, axes, alpha, ws in (("gate", Wg, ("rows", "rows"), cfg.alpha_gate_up, ws_gate),
-                                      ("down", Wd, ("cols", "cols"), cfg.alpha_down, ws_down)):
-        copies = [W0.clone() for _ in range(n_copies)]
-        times = []
-        for it in range(args.stage2_launches + 4):
-            w = copies[it % n_copies]
-            w.copy_(W0)
-            # touch the other copies so this one has left the caches before it is timed
-            for other in copies:
-                if other is not w:
-                    other.add_(0)
-            a, b = ev(), ev()
-            a.record()
-            dass.score_mask_nm(w, norms, axes[0], axes[1], alpha, n_keep, m, workspace=ws)
-            b.record()
-            torch.cuda.synchronize()
-            if it >= 4:
-                times.append(a.elapsed_time(b))
-        del copies
-        cold[name] = {"median_us": statistics.median(times) * 1e3, "min_us": min(times) * 1e3}
     bytes_per_matrix = 2.0 * Wd.numel() * esz     # every weight read once and written once
+    frac_of_hbm = lambda us: bytes_per_matrix / (us * 1e-6) / 1e9 / PEAK_HBM_GBS
+
+    def cold_nm(W0, norm_axis, group_axis, alpha, nk, mm, ws):
+        return cold_launch_us(W0, lambda w: dass.score_mask_nm(w, norms, norm_axis, group_axis, alpha, nk, mm,
+                                                               workspace=ws), args.stage2_launches, n_copies)
+
+    cold = {"gate": cold_nm(Wg, "rows", "rows", cfg.alpha_gate_up, n_keep, m, ws_gate),
+            "down": cold_nm(Wd, "cols", "cols", cfg.alpha_down, n_keep, m, ws_down)}
     s2_gbs = 3 * bytes_per_matrix / (s2_avg * 1e-3) / 1e9
     cold_call_us = (2 * cold["gate"]["median_us"] + cold["down"]["median_us"]) / 3.0
+
+    # ---- the same matrices at 4:8 (the workload names both patterns): a few whole steps for the in-step
+    # figure, then launch by launch ---------------------------------------------------------------
+    stage2_48 = None
+    if (n_keep, m) != (4, 8) and I % 8 == 0:
+        _, _, s2_48, _ = run_steps(cfg, 4, 8, X, Wg, Wu, Wd, max(2, min(args.steps, 5)), 1)
+        c48 = {"gate": cold_nm(Wg, "rows", "rows", cfg.alpha_gate_up, 4, 8, ws_gate),
+               "down": cold_nm(Wd, "cols", "cols", cfg.alpha_down, 4, 8, ws_down)}
+        gbs48 = 3 * bytes_per_matrix / (s2_48 * 1e-3) / 1e9
+        stage2_48 = {"kernel": "nm_half_rows_kernel x2 + nm_half_cols_kernel at 4:8, the three launches of a step, "
+                               "event to event", "bound": "hbm", "achieved": gbs48, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": gbs48 / PEAK_HBM_GBS, "traffic": None,
+                     "in_step_ms_3_matrices": s2_48, "cold_gate_us": c48["gate"], "cold_down_us": c48["down"],
+                     "cold_gate_frac": frac_of_hbm(c48["gate"]["median_us"]),
+                     "cold_down_frac": frac_of_hbm(c48["down"]["median_us"])}
+
+    # ---- the other reading of the group direction: Gate-Proj with groups of M consecutive INPUT weights
+    # (norm along the rows, groups along the columns), launch by launch -----------------------------
+    other_reading = {}
+    for nk, mm in ((2, 4), (4, 8)):
+        c = cold_nm(Wg, "rows", "cols", cfg.alpha_gate_up, nk, mm, ws_gate)
+        other_reading[f"gate_{nk}:{mm}"] = dict(c, frac=frac_of_hbm(c["median_us"]))
+
+    # ---- unstructured selection, 50 % of every comparison group, launch by launch -------------
+    ws_u = torch.empty(max(16, dass.unstructured_workspace_bytes(I, d, Wg.dtype, "rows", "rows"),
+                           dass.unstructured_workspace_bytes(d, I, Wd.dtype, "cols", "cols")),
+                       dtype=torch.uint8, device=dev)
+    unstructured = {}
+    for name, W0, axes, alpha in (("gate", Wg, ("rows", "rows"), cfg.alpha_gate_up),
+                                  ("down", Wd, ("cols", "cols"), cfg.alpha_down)):
+        c = cold_launch_us(W0, lambda w: dass.score_mask_unstructured(w, norms, axes[0], axes[1], alpha, I // 2,
+                                                                      workspace=ws_u),
+                           max(6, args.stage2_launches // 2), n_copies)
+        unstructured[name] = dict(c, GBps=bytes_per_matrix / (c["median_us"] * 1e-6) / 1e9,
+                                  frac=frac_of_hbm(c["median_us"]))
+    unstructured["bound"] = "hbm"
+    unstructured["bytes_per_matrix"] = bytes_per_matrix
+    del ws_u
 
     # ---- the Wanda metric's input-feature norms over the same tokens (reads X once) ------------
     in_sumsq = torch.empty(d, device=dev)
@@ -351,6 +432,36 @@ def main():
                  "compress_24_GBps": {k: cmp_bytes / (v * 1e-6) / 1e9 for k, v in cmp_us.items()}}
         del pruned
 
+    # ---- every other configuration, a few steps each (their tensors replace this workload's) --------
+    others = []
+    names = [] if args.other_configs == "none" else \
+        [n for n in synth.CONFIGS if n != cfg.name] if args.other_configs == "all" else args.other_configs.split(",")
+    x_sample = X[:min(T, 8192)].clone()
+    w_cpu = None
+    if not args.no_cpu_baseline:
+        w_cpu = tuple(w.cpu() for w in (Wg, Wu, Wd))
+    norms_cpu = norms.cpu().numpy()
+    if names:
+        del X
+        torch.cuda.empty_cache()
+    for name in names:
+        oc = synth.CONFIGS[name]
+        onk, om = oc.nm[0]
+        oX, oWg, oWu, oWd = make_inputs(oc, dev)
+        o_ms, o_s1, o_s2, _ = run_steps(oc, onk, om, oX, oWg, oWu, oWd, args.other_steps, 1)
+        o_esz = 2 if oc.dtype == "bf16" else 4
+        o_flops = 4.0 * oc.tokens * oc.d * oc.d_int
+        o_bytes = 3 * 2.0 * oWd.numel() * o_esz
+        others.append({"name": name, "d": oc.d, "d_int": oc.d_int, "tokens": oc.tokens, "chunk": oc.chunk,
+                       "dtype": oc.dtype, "act": oc.act, "nm": f"{onk}:{om}", "steps": args.other_steps,
+                       "ms_per_step": o_ms, "tokens_per_s": oc.tokens / (o_ms * 1e-3),
+                       "stage1_ms": o_s1, "stage1_TFLOPs": o_flops / (o_s1 * 1e-3) / 1e12,
+                       "stage1_frac": (o_flops / (o_s1 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if oc.dtype == "bf16" else None,
+                       "stage2_us_3_matrices": o_s2 * 1e3, "stage2_GBps": o_bytes / (o_s2 * 1e-3) / 1e9,
+                       "stage2_frac": o_bytes / (o_s2 * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        del oX, oWg, oWu, oWd
+        torch.cuda.empty_cache()
+
     out = {
         "metric": "calib tokens/s (fused GLU-norm, %MFMA peak) + N:M mask GB/s, LLaMA2-7B MLP",
         "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -374,15 +485,19 @@ def main():
                    "cold_single_launch_GBps": bytes_per_matrix / (cold_call_us * 1e-6) / 1e9,
                    "bytes_per_matrix": bytes_per_matrix},
     }
+    if stage2_48 is not None:
+        out["roofline_stage2_48"] = stage2_48
+    out["stage2_other_reading"] = other_reading
+    out["unstructured"] = unstructured
+    if others:
+        out["all_configs"] = others
     out["input_norms_eq1"] = input_norms
     if model is not None:
         out["stage2_whole_model"] = model
     if chain is not None:
         out["layer_chaining"] = chain
-    if not args.no_cpu_baseline:
-        n_sample = min(T, 8192)   # about 14 s of the oracle on 16 host threads
-        out["cpu_baseline"] = cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X[:n_sample],
-                                           norms.cpu().numpy())
+    if not args.no_cpu_baseline:   # the first 8192 tokens: about 14 s of the oracle on 16 host threads
+        out["cpu_baseline"] = cpu_baseline(cfg, n_keep, m, w_cpu[0], w_cpu[1], w_cpu[2], x_sample, norms_cpu)
     print(json.dumps(out), flush=True)
 
 
