@@ -18,7 +18,8 @@
  *   - All argument checks happen on the host before the first HIP call, so a
  *     rejected call has touched nothing.
  *   - Inputs must be finite.  The result for NaN or Inf inputs is undefined.
- *   - Thread safe; the only library state is a thread-local error string.
+ *   - Thread safe; the only library state is a thread-local error string
+ *     (and, for dass_score_mask_unstructured_static, one device array).
  */
 #ifndef DASS_H
 #define DASS_H
@@ -212,6 +213,32 @@ dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, in
                                          double alpha, int64_t n_prune, uint8_t *mask_out,
                                          void *workspace, size_t workspace_bytes,
                                          void *hip_stream);
+
+/*
+ * dass_score_mask_unstructured for callers that cannot allocate device memory
+ * and so have no workspace to pass: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (without
+ * the workspace), same result bit for bit.  The factor vector f lives in a
+ * device array of the library's own, 65536 floats (256 KB) on every GPU the
+ * library is used on, held until the process ends; its address is looked up
+ * on the first call on a device (hipGetSymbolAddress).  Nothing is allocated
+ * or freed, by this call or by anything it calls.
+ *
+ *   - The norm axis may be at most 65536 long; beyond that DASS_ERR_WORKSPACE
+ *     (use dass_score_mask_unstructured with a workspace).
+ *   - Column lines of more than 16384 bf16 / 8192 f32 weights are selected
+ *     by the multi-pass kernels (no room for the transposed copy): correct,
+ *     slower.
+ *   - All calls on one GPU share the one array: calls that may overlap there
+ *     (different streams, different threads) race on it; calls in stream
+ *     order on one stream do not.  Every call rewrites the part it reads, so
+ *     nothing needs clearing between calls.
+ */
+dass_status dass_score_mask_unstructured_static(void *W, int64_t rows, int64_t cols, int64_t ld,
+                                                dass_dtype dt, const float *norms,
+                                                dass_axis norm_axis, dass_axis group_axis,
+                                                double alpha, int64_t n_prune,
+                                                uint8_t *mask_out, void *hip_stream);
 
 /*
  * The output of the MLP block (Sec. 2.2 Eq. 2 followed by Eq. 3):

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     mlp_forward, mlp_forward_workspace_bytes, compress_24, down_proj_sparse24,
     score_mask_nm, nm_workspace_bytes,
     score_mask_nm_batched, nm_batched_workspace_bytes,
-    score_mask_unstructured, unstructured_workspace_bytes,
+    score_mask_unstructured, score_mask_unstructured_static, unstructured_workspace_bytes,
     library_path, load_library, version,
 )

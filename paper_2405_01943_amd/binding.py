@@ -24,7 +24,7 @@ EXPORTS = (
     "dass_calib_workspace_bytes", "dass_calib_norms",
     "dass_nm_workspace_bytes", "dass_score_mask_nm",
     "dass_nm_batched_workspace_bytes", "dass_score_mask_nm_batched",
-    "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured",
+    "dass_unstructured_workspace_bytes", "dass_score_mask_unstructured", "dass_score_mask_unstructured_static",
     "dass_input_norms_workspace_bytes", "dass_input_norms",
     "dass_mlp_forward_workspace_bytes", "dass_mlp_forward", "dass_compress_24", "dass_down_proj_sparse24",
     "dass_status_string", "dass_last_error_string", "dass_version",
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.dass_score_mask_unstructured.restype = ci
     lib.dass_score_mask_unstructured.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, i64, vp,
                                                  vp, sz, vp]
+    lib.dass_score_mask_unstructured_static.restype = ci
+    lib.dass_score_mask_unstructured_static.argtypes = [vp, i64, i64, i64, ci, vp, ci, ci, dbl, i64, vp, vp]
     lib.dass_input_norms_workspace_bytes.restype = sz
     lib.dass_input_norms_workspace_bytes.argtypes = [i64, i64]
     lib.dass_input_norms.restype = ci
@@ -336,6 +338,24 @@ def score_mask_unstructured(W: torch.Tensor, norms: torch.Tensor, norm_axis: str
                                             AXIS[norm_axis], AXIS[group_axis], float(alpha),
                                             int(n_prune), _ptr(mask_out), _ptr(workspace), ws_bytes,
                                             _stream(stream)))
+
+
+def score_mask_unstructured_static(W: torch.Tensor, norms: torch.Tensor, norm_axis: str, group_axis: str,
+                                   alpha: float, n_prune: int, mask_out: Optional[torch.Tensor] = None,
+                                   stream=None) -> None:
+    """dass_score_mask_unstructured_static: the same selection with the library's own device scratch."""
+    lib = load_library()
+    rows, cols, ld = _matrix(W, "W")
+    if norms.dtype != torch.float32 or not norms.is_contiguous():
+        raise TypeError("norms: need contiguous float32")
+    if norms.numel() != (rows if norm_axis == "rows" else cols):
+        raise ValueError("norms length does not match norm_axis")
+    if mask_out is not None and (mask_out.dtype != torch.uint8 or not mask_out.is_contiguous()
+                                 or mask_out.numel() != rows * (cols // 8)):
+        raise TypeError("mask_out: need contiguous uint8[rows * cols / 8]")
+    _check(lib.dass_score_mask_unstructured_static(_ptr(W), rows, cols, ld, DTYPE[W.dtype], _ptr(norms),
+                                                   AXIS[norm_axis], AXIS[group_axis], float(alpha),
+                                                   int(n_prune), _ptr(mask_out), _stream(stream)))
 
 
 def compress_24(W: torch.Tensor, group_axis: str, values_out: torch.Tensor, meta_out: torch.Tensor,

@@ -15,6 +15,7 @@
 // wanted number of positions the index passes are skipped.
 #include "select.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace dass {
@@ -1202,18 +1203,19 @@ extern "C" size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, 
     return bytes;
 }
 
-extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, int64_t ld,
-                                                    dass_dtype dt, const float *norms,
-                                                    dass_axis norm_axis, dass_axis group_axis,
-                                                    double alpha, int64_t n_prune,
-                                                    uint8_t *mask_out, void *workspace,
-                                                    size_t workspace_bytes, void *hip_stream)
+namespace dass {
+
+// The selection itself, shared by the two entry points.  `workspace_needed` is what the caller's
+// contract asks for; a workspace that holds the factor vector but not the transposed copy sends
+// long column lines to the multi-pass kernels.
+static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t rows, int64_t cols, int64_t ld,
+                                                dass_dtype dt, const float *norms, dass_axis norm_axis,
+                                                dass_axis group_axis, double alpha, int64_t n_prune,
+                                                uint8_t *mask_out, void *workspace, size_t workspace_bytes,
+                                                size_t workspace_needed, void *hip_stream)
 {
-    using namespace dass;
-    const char *fn = "dass_score_mask_unstructured";
-    dass_status s = check_score_args(
-        fn, W, rows, cols, ld, dt, norms, norm_axis, group_axis, alpha, workspace, workspace_bytes,
-        dass_unstructured_workspace_bytes(rows, cols, dt, norm_axis, group_axis));
+    dass_status s = check_score_args(fn, W, rows, cols, ld, dt, norms, norm_axis, group_axis, alpha, workspace,
+                                     workspace_bytes, workspace_needed);
     if (s != DASS_OK)
         return s;
     const int64_t len = group_axis == DASS_AXIS_ROWS ? rows : cols;
@@ -1287,4 +1289,72 @@ extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64
                            mask_out);
     }
     return check_launch("unstructured kernel");
+}
+
+// ---- device memory of the library's own, for dass_score_mask_unstructured_static ----------
+// The factor vector f = norms^alpha of one call: every GPU the library runs on holds this array
+// until the process ends.  In host code the array's name is only a handle: its address on the
+// current device comes from hipGetSymbolAddress, once per device, and is what kernels are given.
+constexpr int64_t kStaticFactors = 65536;
+static __device__ __align__(256) float scratch[kStaticFactors];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static float *scratch_ptr[kMaxDevices] = {nullptr};
+
+// Address of `scratch` on the current device (looked up on the first call on that device).
+static dass_status static_scratch(const char *fn, float **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return fail(DASS_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(DASS_ERR_HIP, "%s: device ordinal %d outside 0..%d", fn, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(DASS_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+        scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = scratch_ptr[dev];
+    return DASS_OK;
+}
+
+}  // namespace dass
+
+extern "C" dass_status dass_score_mask_unstructured(void *W, int64_t rows, int64_t cols, int64_t ld,
+                                                    dass_dtype dt, const float *norms,
+                                                    dass_axis norm_axis, dass_axis group_axis,
+                                                    double alpha, int64_t n_prune,
+                                                    uint8_t *mask_out, void *workspace,
+                                                    size_t workspace_bytes, void *hip_stream)
+{
+    return dass::score_mask_unstructured_impl("dass_score_mask_unstructured", W, rows, cols, ld, dt, norms, norm_axis,
+                                              group_axis, alpha, n_prune, mask_out, workspace, workspace_bytes,
+                                              dass_unstructured_workspace_bytes(rows, cols, dt, norm_axis, group_axis),
+                                              hip_stream);
+}
+
+extern "C" dass_status dass_score_mask_unstructured_static(void *W, int64_t rows, int64_t cols, int64_t ld,
+                                                           dass_dtype dt, const float *norms,
+                                                           dass_axis norm_axis, dass_axis group_axis,
+                                                           double alpha, int64_t n_prune, uint8_t *mask_out,
+                                                           void *hip_stream)
+{
+    using namespace dass;
+    const char *fn = "dass_score_mask_unstructured_static";
+    const int64_t n_norms = norm_axis == DASS_AXIS_ROWS ? rows : cols;
+    if (n_norms > kStaticFactors)
+        return fail(DASS_ERR_WORKSPACE, "%s: %lld norms exceed the %lld the library's own scratch holds; use "
+                    "dass_score_mask_unstructured with a workspace", fn, (long long)n_norms, (long long)kStaticFactors);
+    float *f = nullptr;
+    const dass_status s = static_scratch(fn, &f);
+    if (s != DASS_OK)
+        return s;
+    const size_t need = n_norms > 0 ? round_up((size_t)n_norms * sizeof(float), 256) : 0;
+    return score_mask_unstructured_impl(fn, W, rows, cols, ld, dt, norms, norm_axis, group_axis, alpha, n_prune,
+                                        mask_out, f, sizeof(float) * (size_t)kStaticFactors, need, hip_stream);
 }

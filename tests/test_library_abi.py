@@ -85,6 +85,13 @@ def test_unstructured_rejections(lib):
     assert call(cols=12) == "DASS_ERR_SHAPE"
 
 
+def test_unstructured_static_size_limit_precedes_any_gpu_call(lib):
+    """More norms than the library's own scratch holds: rejected on the host, with the limit in the text."""
+    rc = lib.dass_score_mask_unstructured_static(FAKE, 65544, 8, 8, 1, FAKE, 0, 1, 1.0, 4, None, None)
+    assert lib.dass_status_string(rc) == b"DASS_ERR_WORKSPACE"
+    assert "65536" in lib.dass_last_error_string().decode()
+
+
 def test_calib_too_many_tiles_is_rejected_before_the_first_launch(lib):
     # 2^31 tiles of 256 tokens: no launch can hold them; sumsq (a fake pointer) is never written
     rc = lib.dass_calib_norms(FAKE, 1 << 40, 64, FAKE, FAKE, 64, 64, 128, 1, 0, FAKE, 0, None, None, 0, None)
