@@ -31,7 +31,16 @@
 extern "C" {
 #endif
 
-typedef enum {
+/* The enumerations below are plain C enums.  A C++ translation unit gives them the fixed
+ * underlying type int (what a C caller passes): a value outside the list, which every entry point
+ * must answer with an error code, is then an ordinary value there and not undefined behaviour. */
+#ifdef __cplusplus
+#define DASS_ENUM(name) enum name : int
+#else
+#define DASS_ENUM(name) enum name
+#endif
+
+typedef DASS_ENUM(dass_status) {
     DASS_OK = 0,
     DASS_ERR_NULL = 1,      /* a required pointer is NULL                        */
     DASS_ERR_SHAPE = 2,     /* non-positive size, ld < width, ragged group axis  */
@@ -42,11 +51,11 @@ typedef enum {
     DASS_ERR_HIP = 7        /* a HIP launch failed; see dass_last_error_string() */
 } dass_status;
 
-typedef enum { DASS_F32 = 0, DASS_BF16 = 1 } dass_dtype;
+typedef DASS_ENUM(dass_dtype) { DASS_F32 = 0, DASS_BF16 = 1 } dass_dtype;
 
 /* sigma(.) of Sec. 2.2 Eq. 2: Swish (beta = 1) for SwiGLU, GeLU (tanh or erf
  * form) for GeGLU, ReLU for ReGLU. */
-typedef enum {
+typedef DASS_ENUM(dass_act) {
     DASS_ACT_SILU = 0,
     DASS_ACT_GELU_TANH = 1,
     DASS_ACT_GELU_ERF = 2,
@@ -54,7 +63,7 @@ typedef enum {
 } dass_act;
 
 /* A dimension of a row-major matrix W[rows, cols]. */
-typedef enum { DASS_AXIS_ROWS = 0, DASS_AXIS_COLS = 1 } dass_axis;
+typedef DASS_ENUM(dass_axis) { DASS_AXIS_ROWS = 0, DASS_AXIS_COLS = 1 } dass_axis;
 
 /*
  * Stage 1 -- calibration statistics (Sec. 2.2 Eq. 2 and Sec. 3 "Incorporating

@@ -37,8 +37,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        # DASS_ORACLE_LIB: another build of dass_oracle.c to load instead (the sanitizer test's)
+        path = os.environ.get("DASS_ORACLE_LIB") or build()
+        lib = ctypes.CDLL(path)
         i64, dbl, vp, ci = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         lib.oracle_act.restype = dbl
         lib.oracle_act.argtypes = [dbl, ci]
