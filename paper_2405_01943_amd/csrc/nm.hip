@@ -7,11 +7,13 @@
 //
 // Two families of kernels:
 //   nm_half_*   the patterns the paper uses, n_keep = m / 2 for m = 2, 4, 8, with
-//               alpha in {0, 0.5, 1}: the factor is computed in the kernel, scores
-//               are exact two-term f32 sums compared a wavefront at a time, the
-//               selection is scalar mask logic, accesses are non-temporal and every
-//               thread makes a single pass (many small workgroups keep HBM busier
-//               than a resident grid that loops).
+//               alpha in {0, 0.5, 1}: the factor is computed in the kernel; a group
+//               is decided by its cut (the m / 2-th largest leading term, from a
+//               min/max network) whenever the leading terms decide it, else by
+//               pairwise comparison of exact two-term f32 scores, bit-sliced over
+//               the thread's groups; accesses are non-temporal and every thread
+//               makes a single pass (many small workgroups keep HBM busier than a
+//               resident grid that loops).
 //   nm_*        every other (n_keep, m, alpha): factor vector from a helper kernel,
 //               scores as f64 products, selection by counting wins per lane.
 #include "select.h"
@@ -93,7 +95,7 @@ __device__ __forceinline__ void zero_at(char *W, int64_t r, int64_t c, int64_t l
 // pieces of up to 4 KB; every thread makes one pass and the grid covers the matrix (many small workgroups
 // keep HBM busier than a resident grid that loops).
 // (`bid`: the workgroup's number inside this matrix.)
-template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool OPTIMISTIC>
+template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool CUT_FIRST>
 __device__ __forceinline__ void nm_half_rows_body(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx, uint32_t bid)
@@ -137,39 +139,87 @@ __device__ __forceinline__ void nm_half_rows_body(
         if constexpr (NORM_ROWS)
             scaled_factors<M, false>(norms + r0, fmode, fr, fast_ok);
 
-        // Outcomes of all pairs of rows, one bit per column (column e ends up in bit e).
-        PairWords<M> pw;
-        float pmax = 0.0f, dmin = 1.0f;
-        auto fill = [&](auto leading_only) {
-            constexpr bool LEADING_ONLY = decltype(leading_only)::value;
+        if constexpr (CUT_FIRST) {
+            // Every column's group against its cut (select.h): M comparisons instead of M (M - 1) / 2
+            // pairs, the result written over the weights in their registers.  A wavefront in which some
+            // group is not decided by its leading terms, or some product left the f32 range, fetches
+            // its weights again (memory still holds them) and takes the pairwise code below.
+            uint32_t kept_cols[M];
 #pragma unroll
-            for (int e = EPV - 1; e >= 0; --e) {
-                float p[M], q[M];
+            for (int a = 0; a < M; ++a)
+                kept_cols[a] = 0;
+            bool undecided = false;
+            float top_all = 0.0f;
+            constexpr int EPW = DT == DASS_BF16 ? 2 : 1;   // elements per 32-bit word
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t part[EPW][M];
+#pragma unroll
+                for (int h = 0; h < EPW; ++h) {
+                    const int e = j * EPW + h;
+                    float x[M], p[M];
+#pragma unroll
+                    for (int a = 0; a < M; ++a) {
+                        x[a] = elem_of<DT>(v[g][a], e);
+                        p[a] = fabsf(x[a]) * (NORM_ROWS ? fr[a] : fc[e]);
+                    }
+                    float cut, next, top;
+                    group_cut<M>(p, cut, next, top);
+                    undecided |= next == cut;
+                    top_all = fmaxf(top_all, top);
+#pragma unroll
+                    for (int a = 0; a < M; ++a) {
+                        const bool keep = p[a] >= cut;
+                        part[h][a] = keep ? __float_as_uint(x[a]) : 0u;
+                        if constexpr (WITH_MASK)
+                            kept_cols[a] |= keep ? 1u << e : 0u;
+                    }
+                }
 #pragma unroll
                 for (int a = 0; a < M; ++a) {
-                    const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[a] : fc[e];
-                    p[a] = w * f;
-                    q[a] = LEADING_ONLY ? 0.0f : fmaf(w, f, -p[a]);
-                    pmax = fmaxf(pmax, p[a]);
+                    if constexpr (DT == DASS_BF16)
+                        v[g][a][j] = pack_bf16_pair(part[0][a], part[1][a]);
+                    else
+                        v[g][a][j] = part[0][a];
                 }
-                push_group<M, LEADING_ONLY>(pw, p, q, dmin);
-                __builtin_amdgcn_sched_barrier(0);   // one column at a time keeps the register count down
+                __builtin_amdgcn_sched_barrier(0);   // one word of columns at a time keeps the register count down
             }
-        };
-        if constexpr (OPTIMISTIC) {
-            fill(std::true_type{});
-            if (__builtin_amdgcn_ballot_w64(dmin == 0.0f) != 0) {   // two equal leading terms somewhere
-                // (the weights pass through an empty asm so that the second pass recomputes its
-                // products instead of keeping all of the first pass's alive)
+            if (__builtin_amdgcn_ballot_w64(undecided || !fast_ok || !(top_all < INFINITY)) == 0) {
 #pragma unroll
-                for (int a = 0; a < M; ++a)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        asm volatile("" : "+v"(v[g][a][j]));
-                fill(std::false_type{});
+                for (int a = 0; a < M; ++a) {
+                    __builtin_nontemporal_store(v[g][a], reinterpret_cast<u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
+                    if constexpr (WITH_MASK) {
+                        if constexpr (EPV == 8) {
+                            mask[(r0 + a) * (cols / 8) + slot] = (uint8_t)kept_cols[a];
+                        } else {   // two lanes share a byte: the even lane writes both halves
+                            const uint32_t other = __shfl_xor(kept_cols[a], 1, 64);
+                            if ((slot & 1) == 0)
+                                mask[(r0 + a) * (cols / 8) + slot / 2] = (uint8_t)(kept_cols[a] | (other << 4));
+                        }
+                    }
+                }
+                continue;
             }
-        } else {
-            fill(std::false_type{});
+#pragma unroll
+            for (int a = 0; a < M; ++a)
+                v[g][a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + ((r0 + a) * ld + c0) * EB));
+        }
+
+        // Outcomes of all pairs of rows, one bit per column (column e ends up in bit e).
+        PairWords<M> pw;
+        float pmax = 0.0f;
+#pragma unroll
+        for (int e = EPV - 1; e >= 0; --e) {
+            float p[M], q[M];
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const float w = fabsf(elem_of<DT>(v[g][a], e)), f = NORM_ROWS ? fr[a] : fc[e];
+                p[a] = w * f;
+                q[a] = fmaf(w, f, -p[a]);
+                pmax = fmaxf(pmax, p[a]);
+            }
+            push_group<M>(pw, p, q);
+            __builtin_amdgcn_sched_barrier(0);   // one column at a time keeps the register count down
         }
         uint32_t keep[M];
         keep_words<M>(pw, keep);
@@ -235,7 +285,7 @@ __device__ __forceinline__ void nm_half_rows_body(
 // Groups run along a row (contiguous): Down-Proj.  A thread owns the UW = max(EPV, M)
 // consecutive columns of NV 16-byte vectors and RB rows, RB * UW / M groups; the factors of
 // its columns are computed once.
-template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool OPTIMISTIC>
+template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool CUT_FIRST>
 __device__ __forceinline__ void nm_half_cols_body(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx, uint32_t bid)
@@ -276,44 +326,110 @@ __device__ __forceinline__ void nm_half_cols_body(
             scaled_factors<1, false>(norms + (by * RB + k < rows ? by * RB + k : rows - 1), fmode, frow + k, fast_ok);
     }
 
-    // Outcomes of all pairs of positions; group g of row k ends up in bit k * GPR + g.
-    PairWords<M> pw;
-    float pmax = 0.0f, dmin = 1.0f;
-    auto fill = [&](auto leading_only) {
-        constexpr bool LEADING_ONLY = decltype(leading_only)::value;
+    if constexpr (CUT_FIRST) {
+        // Every group against its cut, as in nm_half_rows_body: the result overwrites the weights in
+        // their registers and is stored only if every group of the wavefront was decided by its
+        // leading terms; otherwise the weights are fetched again.
+        uint32_t kept_row[RB];
+        bool undecided = false;
+        float top_all = 0.0f;
+        const int rows_here = rows - by * RB < RB ? (int)(rows - by * RB) : RB;   // uniform in the workgroup
 #pragma unroll
-        for (int k = RB - 1; k >= 0; --k) {
+        for (int k = 0; k < RB; ++k) {
+            kept_row[k] = 0;
+            if (k >= rows_here)
+                break;
             const float fr = NORM_COLS ? 0.0f : frow[k];
+            uint32_t part[UW];
 #pragma unroll
-            for (int g = GPR - 1; g >= 0; --g) {
-                float p[M], q[M];
+            for (int g = 0; g < GPR; ++g) {
+                float x[M], p[M];
 #pragma unroll
                 for (int a = 0; a < M; ++a) {
                     const int e = g * M + a;
-                    const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr;
-                    p[a] = w * f;
-                    q[a] = LEADING_ONLY ? 0.0f : fmaf(w, f, -p[a]);
-                    pmax = fmaxf(pmax, p[a]);
+                    x[a] = elem_of<DT>(v[k][e / EPV], e % EPV);
+                    p[a] = fabsf(x[a]) * (NORM_COLS ? fc[e] : fr);
                 }
-                push_group<M, LEADING_ONLY>(pw, p, q, dmin);
+                float cut, next, top;
+                group_cut<M>(p, cut, next, top);
+                undecided |= next == cut;
+                top_all = fmaxf(top_all, top);
+#pragma unroll
+                for (int a = 0; a < M; ++a) {
+                    const bool keep = p[a] >= cut;
+                    part[g * M + a] = keep ? __float_as_uint(x[a]) : 0u;
+                    if constexpr (WITH_MASK)
+                        kept_row[k] |= keep ? 1u << (g * M + a) : 0u;
+                }
                 __builtin_amdgcn_sched_barrier(0);   // one group at a time keeps the register count down
             }
-        }
-    };
-    if constexpr (OPTIMISTIC) {
-        fill(std::true_type{});
-        if (__builtin_amdgcn_ballot_w64(dmin == 0.0f) != 0) {   // two equal leading terms somewhere
 #pragma unroll
-            for (int k = 0; k < RB; ++k)   // see nm_half_rows_kernel
+            for (int j = 0; j < NV; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (DT == DASS_BF16)
+                        v[k][j][i] = pack_bf16_pair(part[j * 8 + 2 * i], part[j * 8 + 2 * i + 1]);
+                    else
+                        v[k][j][i] = part[j * 4 + i];
+                }
+        }
+        if (__builtin_amdgcn_ballot_w64(undecided || !fast_ok || !(top_all < INFINITY)) == 0) {
+#pragma unroll
+            for (int k = 0; k < RB; ++k) {
+                if (k >= rows_here)
+                    break;
+                const int64_t r = by * RB + k;
+                if (active) {
+#pragma unroll
+                    for (int j = 0; j < NV; ++j)
+                        __builtin_nontemporal_store(v[k][j], reinterpret_cast<u32x4 *>(W + (r * ld + c0) * EB + 16 * j));
+                }
+                if constexpr (WITH_MASK) {
+                    if constexpr (UW >= 8) {
+                        if (active) {
+#pragma unroll
+                            for (int b = 0; b < UW / 8; ++b)
+                                mask[r * (cols / 8) + c0 / 8 + b] = (uint8_t)(kept_row[k] >> (8 * b));
+                        }
+                    } else {
+                        const uint32_t other = __shfl_xor(kept_row[k], 1, 64);
+                        if (active && (slot & 1) == 0)
+                            mask[r * (cols / 8) + slot / 2] = (uint8_t)(kept_row[k] | (other << 4));
+                    }
+                }
+            }
+            return;
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k)
+            if (k < rows_here) {
 #pragma unroll
                 for (int j = 0; j < NV; ++j)
+                    v[k][j] = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4 *>(W + ((by * RB + k) * ld + c0) * EB + 16 * j));
+            }
+    }
+
+    // Outcomes of all pairs of positions; group g of row k ends up in bit k * GPR + g.
+    PairWords<M> pw;
+    float pmax = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        asm volatile("" : "+v"(v[k][j][i]));
-            fill(std::false_type{});
+    for (int k = RB - 1; k >= 0; --k) {
+        const float fr = NORM_COLS ? 0.0f : frow[k];
+#pragma unroll
+        for (int g = GPR - 1; g >= 0; --g) {
+            float p[M], q[M];
+#pragma unroll
+            for (int a = 0; a < M; ++a) {
+                const int e = g * M + a;
+                const float w = fabsf(elem_of<DT>(v[k][e / EPV], e % EPV)), f = NORM_COLS ? fc[e] : fr;
+                p[a] = w * f;
+                q[a] = fmaf(w, f, -p[a]);
+                pmax = fmaxf(pmax, p[a]);
+            }
+            push_group<M>(pw, p, q);
+            __builtin_amdgcn_sched_barrier(0);   // one group at a time keeps the register count down
         }
-    } else {
-        fill(std::false_type{});
     }
     uint32_t keep[M];
     keep_words<M>(pw, keep);
@@ -387,20 +503,20 @@ __device__ __forceinline__ void nm_half_cols_body(
 // ===========================================================================
 
 // One matrix per launch.
-template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool OPTIMISTIC>
+template <int DT, int M, bool NORM_ROWS, bool WITH_MASK, bool CUT_FIRST>
 __global__ __launch_bounds__(kBlock) void nm_half_rows_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
 {
-    nm_half_rows_body<DT, M, NORM_ROWS, WITH_MASK, OPTIMISTIC>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
+    nm_half_rows_body<DT, M, NORM_ROWS, WITH_MASK, CUT_FIRST>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
                                                                blockIdx.x);
 }
-template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool OPTIMISTIC>
+template <int DT, int M, bool NORM_COLS, bool WITH_MASK, bool CUT_FIRST>
 __global__ __launch_bounds__(kBlock) void nm_half_cols_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint8_t *__restrict__ mask, uint32_t nbx)
 {
-    nm_half_cols_body<DT, M, NORM_COLS, WITH_MASK, OPTIMISTIC>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
+    nm_half_cols_body<DT, M, NORM_COLS, WITH_MASK, CUT_FIRST>(Wv, rows, cols, ld, norms, fmode, mask, nbx,
                                                                blockIdx.x);
 }
 
@@ -416,15 +532,15 @@ struct NmBatch {
     int fmode;
     uint32_t nbx, blocks_per_matrix;
 };
-template <int DT, int M, bool GROUPS_DOWN_ROWS, bool NORM_ALONG, bool WITH_MASK, bool OPTIMISTIC>
+template <int DT, int M, bool GROUPS_DOWN_ROWS, bool NORM_ALONG, bool WITH_MASK, bool CUT_FIRST>
 __global__ __launch_bounds__(kBlock) void nm_half_batched_kernel(const NmBatch b)
 {
     const uint32_t k = blockIdx.x / b.blocks_per_matrix, bid = blockIdx.x - k * b.blocks_per_matrix;
     if constexpr (GROUPS_DOWN_ROWS)
-        nm_half_rows_body<DT, M, NORM_ALONG, WITH_MASK, OPTIMISTIC>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
+        nm_half_rows_body<DT, M, NORM_ALONG, WITH_MASK, CUT_FIRST>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
                                                                     WITH_MASK ? b.mask[k] : nullptr, b.nbx, bid);
     else
-        nm_half_cols_body<DT, M, NORM_ALONG, WITH_MASK, OPTIMISTIC>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
+        nm_half_cols_body<DT, M, NORM_ALONG, WITH_MASK, CUT_FIRST>(b.W[k], b.rows, b.cols, b.ld, b.norms[k], b.fmode,
                                                                     WITH_MASK ? b.mask[k] : nullptr, b.nbx, bid);
 }
 
@@ -668,17 +784,19 @@ static nm_kernel_t pick_kernel_m(int m, int group_axis, int norm_axis)
 using nm_half_kernel_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint8_t *,
                                   uint32_t);
 
-// With 8 positions per group the 28 comparisons dominate the kernel, so it first compares the
-// leading terms only (OPTIMISTIC) when ties between them are unlikely: the factor varies
-// inside a group, i.e. it runs along the group axis and alpha is not 0.  A factor that is
-// constant inside the groups leaves bf16 magnitudes to tie all the time; then, and for
-// m < 8 where the kernel is bound by memory anyway, both terms are compared straight away.
+// When the factor varies inside a group (it runs along the group axis and alpha is not 0: the
+// DaSS configuration) two leading terms of a group are almost never equal, and the kernels decide
+// every group by its cut first (CUT_FIRST, select.h): M comparisons per group where the pairwise
+// form needs M (M - 1) / 2, which at 8 positions per group is the difference between a kernel
+// bound by memory and one bound by its arithmetic.  A factor that is constant inside the groups
+// (magnitude pruning, groups across the norm axis) leaves bf16 magnitudes to tie at the cut all
+// the time; those kernels compare pairs with both score terms straight away.
 template <int DT, int M, bool WITH_MASK>
 static nm_half_kernel_t pick_half_kernel(int group_axis, int norm_axis, bool varying_factor)
 {
-    if (M == 8 && varying_factor)
-        return group_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK, M == 8>
-                                            : nm_half_rows_kernel<DT, M, true, WITH_MASK, M == 8>;
+    if (varying_factor)
+        return group_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK, true>
+                                            : nm_half_rows_kernel<DT, M, true, WITH_MASK, true>;
     if (group_axis == DASS_AXIS_COLS)
         return norm_axis == DASS_AXIS_COLS ? nm_half_cols_kernel<DT, M, true, WITH_MASK, false>
                                            : nm_half_cols_kernel<DT, M, false, WITH_MASK, false>;
@@ -711,9 +829,9 @@ template <int DT, int M, bool WITH_MASK>
 static nm_batched_kernel_t pick_batched_kernel(int group_axis, int norm_axis, bool varying_factor)
 {
     const bool down_rows = group_axis == DASS_AXIS_ROWS, along = norm_axis == group_axis;
-    if (M == 8 && varying_factor)   // see pick_half_kernel
-        return down_rows ? nm_half_batched_kernel<DT, M, true, true, WITH_MASK, M == 8>
-                         : nm_half_batched_kernel<DT, M, false, true, WITH_MASK, M == 8>;
+    if (varying_factor)   // see pick_half_kernel
+        return down_rows ? nm_half_batched_kernel<DT, M, true, true, WITH_MASK, true>
+                         : nm_half_batched_kernel<DT, M, false, true, WITH_MASK, true>;
     if (down_rows)
         return along ? nm_half_batched_kernel<DT, M, true, true, WITH_MASK, false>
                      : nm_half_batched_kernel<DT, M, true, false, WITH_MASK, false>;

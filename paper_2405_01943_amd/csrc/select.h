@@ -101,24 +101,15 @@ struct PairWords {
 
 // Shift the outcomes of one more group into the pair words: the new bit 0 of pair (a, b) is
 // set iff b's score is strictly greater than a's (on a tie the earlier position, a, ranks higher).
-// LEADING_ONLY compares the leading terms p alone, which decides every pair whose leading
-// terms differ, and lowers dmin to 0 when two are equal: the caller must then push all of
-// the thread's groups again with both terms.
-template <int M, bool LEADING_ONLY>
-__device__ __forceinline__ void push_group(PairWords<M> &pw, const float *p, const float *q, float &dmin)
+template <int M>
+__device__ __forceinline__ void push_group(PairWords<M> &pw, const float *p, const float *q)
 {
     int n = 0;
 #pragma unroll
     for (int a = 0; a < M; ++a)
 #pragma unroll
         for (int b = a + 1; b < M; ++b) {
-            float t;
-            if constexpr (LEADING_ONLY) {
-                t = p[a] - p[b];
-                dmin = fminf(dmin, fabsf(t));
-            } else {
-                t = fmaf(p[a] - p[b], 4.0f, q[a] - q[b]);
-            }
+            const float t = fmaf(p[a] - p[b], 4.0f, q[a] - q[b]);
             pw.w[n] = __builtin_amdgcn_alignbit(pw.w[n], __float_as_uint(t), 31);   // (w << 1) | sign(t)
             // Pin the word here: otherwise the compiler sinks every push below the caller's
             // range check and keeps all scores of the thread live until then.
@@ -162,6 +153,67 @@ __device__ __forceinline__ void keep_words(const PairWords<M> &pw, uint32_t *kee
             keep[a] = majority3(c1, c2, c3);
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// The cut of a group: the M / 2-th largest leading term (`cut`), the next one below it in
+// rank (`next`) and the largest (`top`), from min/max networks (no comparisons of pairs).
+//
+// Rounding is monotonic: s_a <= s_b for the exact scores implies p_a <= p_b for their leading
+// terms.  So when next < cut strictly, the M / 2 positions with p >= cut are exactly the M / 2
+// best by exact score and no two scores tie across the cut: the group is decided by M
+// comparisons against `cut`, whatever the error terms and the indices are.  When next == cut
+// the leading terms do not decide the group and the caller takes the exact pairwise path.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void sort2(float &lo, float &hi)
+{
+    const float a = __builtin_fminf(lo, hi), b = __builtin_fmaxf(lo, hi);
+    lo = a;
+    hi = b;
+}
+// ascending order of four
+__device__ __forceinline__ void sort4(float &a, float &b, float &c, float &d)
+{
+    sort2(a, b);
+    sort2(c, d);
+    sort2(a, c);   // a: least of the four
+    sort2(b, d);   // d: greatest
+    sort2(b, c);
+}
+template <int M>
+__device__ __forceinline__ void group_cut(const float *p, float &cut, float &next, float &top)
+{
+    static_assert(M == 2 || M == 4 || M == 8, "patterns 1:2, 2:4 and 4:8");
+    if constexpr (M == 2) {
+        cut = top = __builtin_fmaxf(p[0], p[1]);
+        next = __builtin_fminf(p[0], p[1]);
+    } else if constexpr (M == 4) {
+        float a = p[0], b = p[1], c = p[2], d = p[3];
+        sort2(a, b);
+        sort2(c, d);
+        top = __builtin_fmaxf(b, d);
+        const float h = __builtin_fminf(b, d), l = __builtin_fmaxf(a, c);   // the two middle ones, in some order
+        cut = __builtin_fmaxf(h, l);
+        next = __builtin_fminf(h, l);
+    } else {
+        float a0 = p[0], a1 = p[1], a2 = p[2], a3 = p[3], b0 = p[4], b1 = p[5], b2 = p[6], b3 = p[7];
+        sort4(a0, a1, a2, a3);
+        sort4(b0, b1, b2, b3);
+        top = __builtin_fmaxf(a3, b3);
+        // a ascending followed by b descending is bitonic: element i against element i + 4 splits the
+        // eight into the four largest (the maxima) and the four smallest (the minima)
+        cut = __builtin_fminf(__builtin_fminf(__builtin_fmaxf(a0, b3), __builtin_fmaxf(a1, b2)),
+                              __builtin_fminf(__builtin_fmaxf(a2, b1), __builtin_fmaxf(a3, b0)));
+        next = __builtin_fmaxf(__builtin_fmaxf(__builtin_fminf(a0, b3), __builtin_fminf(a1, b2)),
+                               __builtin_fmaxf(__builtin_fminf(a2, b1), __builtin_fminf(a3, b0)));
+    }
+}
+
+// Two bf16 elements, each held as f32 bits with the low half clear, packed into one word:
+// `lo` becomes the low half, `hi` the high half.
+__device__ __forceinline__ uint32_t pack_bf16_pair(uint32_t lo, uint32_t hi)
+{
+    return (lo >> 16) | hi;
 }
 
 // All-ones if bit `bit` of `word` is set, else 0.
