@@ -31,6 +31,7 @@ namespace dass {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // one 16-byte chunk = 8 bf16
 
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 {
     constexpr int BM = P_BM, BN = P_BN, BK = 64, WN = 2;
     constexpr int BN_TILE = EPI == kEpiGemm ? 2 * BN : BN;   // rows of W (output columns) per tile
-    constexpr int TM = 128, TN = 64, MI = 4, NI = 2;
+    constexpr int TM = 128, TN = 64, MI = 8, NI = 4;   // wavefront tile in 16 x 16 MFMA blocks
     constexpr int CH = BK / 8;               // 16-byte chunks per tile row
     constexpr int UNIT = 32768;              // A part, or gate half + up half of the B part
     constexpr int B_HALF = BN * BK * 2;      // 16 KB
@@ -448,45 +449,45 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
                 ru, (lds_ptr_t)(lds64 + unit * UNIT + B_HALF + (wave * B_WL + q - B_WL) * 1024), 16, b_off[q - B_WL], kb, 0, 0);
     };
 
-    f32x16 acc_g[MI][NI], acc_u[MI][NI];
+    f32x4 acc_g[MI][NI], acc_u[MI][NI];
 
-    // ---- LDS -> registers.  A lane holds tile row (lane % 32) and K chunk kk * 2 + lane / 32 of
-    // K step kk (0..3); kk * 2 and lane / 32 occupy different bits, so the byte offset inside a
-    // unit is that of K step 0 XOR kk * 32.
-    const int fr = lane & 31, fc = lane >> 5;
-    int a_frag[MI], b_frag[NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        const int r = wm * TM + i * 32 + fr;
-        a_frag[i] = (r * CH + swizzle<CH>(r, fc)) * 16;
-    }
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int r = wn * TN + j * 32 + fr;
-        b_frag[j] = (r * CH + swizzle<CH>(r, fc)) * 16;
+    // ---- LDS -> registers.  The MFMA is v_mfma_f32_16x16x32_bf16: a lane holds tile row
+    // (lane % 16) of a 16-row block and K chunk kk * 4 + lane / 16 of K step kk (0, 1: 32 columns
+    // each); kk * 4 and lane / 16 occupy different bits, so the byte offset inside a unit is that
+    // of K step 0 XOR kk * 64.  Blocks of 16 rows are 2048 bytes apart and swizzled alike.
+    int a_frag0, b_frag0;
+    {
+        const int fr = lane & 15, fc = lane >> 4;
+        const int ra = wm * TM + fr, rb = wn * TN + fr;
+        a_frag0 = (ra * CH + swizzle<CH>(ra, fc)) * 16;
+        b_frag0 = (rb * CH + swizzle<CH>(rb, fc)) * 16;
     }
     struct Frags {
         bf16x8 a[MI], g[NI], u[NI];
     };
-    // q-th fragment of K step kk of the slab in units (ua, ub), in the order the MFMAs need them
+    constexpr int N_READS = MI + 2 * NI;   // 16 fragment reads per K step
+    // q-th fragment of K step kk of the slab in units (ua, ub), in the order the MFMAs need them:
+    // a0 g0 u0 g1 u1 g2 u2 g3 u3 a1 .. a7
     auto read_one = [&](Frags &f, int ua, int ub, int kk, int q) {
-        const char *pa = lds64 + ua * UNIT, *pb = lds64 + ub * UNIT;
-        const int x = kk * 32;
-        switch (q) {
-        case 0: f.a[0] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[0] ^ x)); break;
-        case 1: f.g[0] = *reinterpret_cast<const bf16x8 *>(pb + (b_frag[0] ^ x)); break;
-        case 2: f.u[0] = *reinterpret_cast<const bf16x8 *>(pb + B_HALF + (b_frag[0] ^ x)); break;
-        case 3: f.g[1] = *reinterpret_cast<const bf16x8 *>(pb + (b_frag[1] ^ x)); break;
-        case 4: f.u[1] = *reinterpret_cast<const bf16x8 *>(pb + B_HALF + (b_frag[1] ^ x)); break;
-        case 5: f.a[1] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[1] ^ x)); break;
-        case 6: f.a[2] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[2] ^ x)); break;
-        default: f.a[3] = *reinterpret_cast<const bf16x8 *>(pa + (a_frag[3] ^ x)); break;
+        const char *pa = lds64 + ua * UNIT + (a_frag0 ^ (kk * 64)), *pb = lds64 + ub * UNIT + (b_frag0 ^ (kk * 64));
+        if (q == 0) {
+            f.a[0] = *reinterpret_cast<const bf16x8 *>(pa);
+        } else if (q <= 2 * NI) {
+            const int j = (q - 1) >> 1;
+            if ((q - 1) & 1)
+                f.u[j] = *reinterpret_cast<const bf16x8 *>(pb + B_HALF + j * 2048);
+            else
+                f.g[j] = *reinterpret_cast<const bf16x8 *>(pb + j * 2048);
+        } else {
+            const int i = q - 2 * NI;
+            f.a[i] = *reinterpret_cast<const bf16x8 *>(pa + i * 2048);
         }
     };
+    constexpr int N_PAIRS = MI * NI;   // 32 gate/up MFMA pairs per K step
     auto mfma_pair = [&](const Frags &f, int q) {
-        const int i = q >> 1, j = q & 1;
-        acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
-        acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
+        const int i = q / NI, j = q % NI;
+        acc_g[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
+        acc_u[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
     };
 
     // ---- prologue: A0 B0 A1 B1 A2 fill the five units
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 4; ++r) {
                 acc_g[i][j][r] = 0.0f;
                 acc_u[i][j][r] = 0.0f;
             }
@@ -528,18 +529,19 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
     block_barrier();
     Frags f0, f1;
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int q = 0; q < N_READS; ++q)
         read_one(f0, 0, 1, 0, q);
 
-    // ---- main loop.  One slab = 4 K steps of 8 gate/up MFMA pairs, alternately on f0 and f1;
-    // the first pairs of a K step carry the fragment reads of the next one (2 2 1 1 1 1 per
-    // pair).  Between the barrier of slab s - 1 and that of slab s a wavefront issues the B part
-    // of slab s + 1 (K step 3 of slab s - 1, K step 0 of slab s) and the A part of slab s + 2
-    // (K steps 1 and 2).  B1, A2, B2: whether these parts exist and were not issued by the
-    // prologue; NEXT: whether a slab follows.  All four are compile-time, so the steady state
-    // has no branch between its MFMAs.
+    // ---- main loop.  One slab = 2 K steps of 32 gate/up MFMA pairs, the first on f0, the second
+    // on f1.  During K step 0 a wavefront reads the fragments of K step 1 (one read every second
+    // pair); during the second half of K step 1, after the slab's one barrier, those of K step 0
+    // of the next slab (one read a pair).  One global->LDS wave-load goes out every fourth pair:
+    // the rest of the B part of slab s + 1 (first half of K step 0), then the A part of slab s + 2
+    // (up to the barrier), then the first half of the B part of slab s + 2 into the A unit of
+    // slab s, which is free once every wavefront holds its last fragments of slab s.  B1, A2, B2:
+    // whether these parts exist and were not issued by the prologue; NEXT: whether a slab follows.
+    // All four are compile-time, so the steady state has no branch between its MFMAs.
     int ua = 0, ub = 1;   // ring units of slab s
-    constexpr int first_read[9] = {0, 2, 4, 5, 6, 7, 8, 8, 8};
     auto slab_body = [&](int s, auto b1_tag, auto a2_tag, auto b2_tag, auto next_tag) {
         constexpr bool B1 = decltype(b1_tag)::value, A2 = decltype(a2_tag)::value, B2 = decltype(b2_tag)::value,
                        NEXT = decltype(next_tag)::value;
@@ -547,33 +549,21 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
         const int uam = ua >= 2 ? ua - 2 : ua + 3, ubm = ub >= 2 ? ub - 2 : ub + 3;           // units of slab s - 1
         const int k1 = (s + 1) * BK * 2, k2 = (s + 2) * BK * 2;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {   // K step 0
-            if (B1 && (q & 1) == 0)
-                issue_b(uam, k1, 4 + (q >> 1));
-#pragma unroll
-            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                read_one(f1, ua, ub, 1, r);
+        for (int q = 0; q < N_PAIRS; ++q) {   // K step 0
+            if (B1 && q < N_PAIRS / 2 && (q & 3) == 0)
+                issue_b(uam, k1, 4 + (q >> 2));
+            if (A2 && q >= N_PAIRS / 2 && (q & 3) == 0)
+                issue_a(ubm, k2, (q - N_PAIRS / 2) >> 2);
+            if ((q & 1) == 0)
+                read_one(f1, ua, ub, 1, q >> 1);
             mfma_pair(f0, q);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {   // K step 1
-            if (A2 && (q & 1) == 0)
-                issue_a(ubm, k2, q >> 1);
-#pragma unroll
-            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                read_one(f0, ua, ub, 2, r);
+        for (int q = 0; q < N_PAIRS / 2; ++q) {   // K step 1, first half
+            if (A2 && (q & 3) == 0)
+                issue_a(ubm, k2, 4 + (q >> 2));
             mfma_pair(f1, q);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {   // K step 2
-            if (A2 && (q & 1) == 0)
-                issue_a(ubm, k2, 4 + (q >> 1));
-#pragma unroll
-            for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                read_one(f1, ua, ub, 3, r);
-            mfma_pair(f0, q);
             __builtin_amdgcn_sched_barrier(0);
         }
         // Slab s + 1 has landed (only the A part of slab s + 2, the last 8 loads, may be in
@@ -584,14 +574,11 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
             __builtin_amdgcn_s_waitcnt(0x0070);
         block_barrier();
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {   // K step 3; the units of slab s are free
-            if (B2 && (q & 1) == 0)
-                issue_b(ua, k2, q >> 1);
-            if (NEXT) {
-#pragma unroll
-                for (int r = first_read[q]; r < first_read[q + 1]; ++r)
-                    read_one(f0, ua1, ub1, 0, r);
-            }
+        for (int q = N_PAIRS / 2; q < N_PAIRS; ++q) {   // K step 1, second half; the units of slab s are free
+            if (B2 && (q & 3) == 0)
+                issue_b(ua, k2, (q - N_PAIRS / 2) >> 2);
+            if (NEXT)
+                read_one(f0, ua1, ub1, 0, q - N_PAIRS / 2);
             mfma_pair(f1, q);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -616,26 +603,28 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 
     if constexpr (EPI == kEpiNorms) {
         // ---- epilogue: y = act(g) * u, squared and summed over the tile's tokens (tokens are the
-        // MFMA's M index: a lane's 16 registers of a block belong to one neuron).  Tokens past T
-        // were read as zeros, so their y is 0 and no test is needed.  The lane's neuron index is
-        // derived here from the lane number afresh: nothing per-lane has to survive the main loop
-        // for it (the loop uses every register, and a spill would give the kernel a scratch segment).
+        // MFMA's M index: the 4 registers a lane holds of a 16 x 16 block are rows 4 (lane / 16) ..
+        // + 3 of column lane % 16, i.e. 4 tokens of one neuron).  Tokens past T were read as zeros, so
+        // their y is 0 and no test is needed.  The lane's neuron index is derived here from the lane
+        // number afresh: nothing per-lane has to survive the main loop for it (a spill would give
+        // the kernel a scratch segment).
         uint32_t lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
         asm volatile("" : "+v"(lane_e));
-        const int fr_e = lane_e & 31, fc_e = lane_e >> 5;
+        const int fr_e = lane_e & 15, fc_e = lane_e >> 4;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             float part = 0.0f;
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
+                for (int r = 0; r < 4; ++r) {
                     const float y = glu_act_fast<ACT>(acc_g[i][j][r]) * acc_u[i][j][r];
                     part = fmaf(y, y, part);
                 }
             }
+            part += __shfl_xor(part, 16, 64);
             part += __shfl_xor(part, 32, 64);
-            const int64_t n = n0 + wn * TN + j * 32 + fr_e;
+            const int64_t n = n0 + wn * TN + j * 16 + fr_e;
             if (fc_e == 0 && n < d_int)
                 atomicAdd(sumsq + n, part);
         }
@@ -649,6 +638,9 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
         // A lane holds rows r and r + 1 (registers 2 k, 2 k + 1) of column fr; with its neighbour
         // fr ^ 1 it trades one of them, so that even lanes own row 2 k and odd lanes row 2 k + 1
         // of the column pair: one 32-bit LDS write each.
+        uint32_t lane_s = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));   // afresh, as above
+        asm volatile("" : "+v"(lane_s));
+        const int fr = lane_s & 15, fc = lane_s >> 4;
         auto put_pair = [&](float v0, float v1, int row_even, int col_base) {
             const bool odd = fr & 1;
             const float mine = odd ? v1 : v0, send = odd ? v0 : v1;
@@ -662,9 +654,9 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int row_even = wm * TM + i * 32 + 8 * (k / 2) + 4 * fc + 2 * (k % 2);
-                    const int col_base = wn * TN + j * 32;
+                for (int k = 0; k < 2; ++k) {
+                    const int row_even = wm * TM + i * 16 + 4 * fc + 2 * k;
+                    const int col_base = wn * TN + j * 16;
                     if constexpr (EPI == kEpiGlu) {
                         put_pair(glu_act_fast<ACT>(acc_g[i][j][2 * k]) * acc_u[i][j][2 * k],
                                  glu_act_fast<ACT>(acc_g[i][j][2 * k + 1]) * acc_u[i][j][2 * k + 1], row_even, col_base);
