@@ -49,7 +49,18 @@ __device__ __forceinline__ float glu_act_fast(float g)
         const float e = g * fmaf(-0.10294324f, g * g, -2.3022082f);
         return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(e));
     } else if constexpr (ACT == DASS_ACT_GELU_ERF) {
-        return 0.5f * g * (1.0f + erff(g * 0.7071067811865476f));
+        // erf by the classical five-term rational form in t = 1 / (1 + p z) times exp(-z^2)
+        // (Abramowitz & Stegun 7.1.26, absolute error of erf below 1.5e-7), written on z = |g| / sqrt(2)
+        // so that neither branch cancels: with h = (1 - erf z) / 2 = P(t) exp(-g^2 / 2) / 2,
+        // GELU(g) = g (1 - h) for g >= 0 and g h for g < 0.  The library's erff is several times the
+        // instructions; the norms are good to 1e-6 either way.
+        const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(g), 0.3275911f * 0.70710678f, 1.0f));
+        float P = fmaf(t, 1.061405429f, -1.453152027f);
+        P = fmaf(t, P, 1.421413741f);
+        P = fmaf(t, P, -0.284496736f);
+        P = fmaf(t, P, 0.254829592f);
+        const float h = 0.5f * t * P * __builtin_amdgcn_exp2f(g * g * -0.72134752f);   // exp(-g^2 / 2)
+        return g * (g >= 0.0f ? 1.0f - h : h);
     } else {
         return fmaxf(g, 0.0f);
     }
