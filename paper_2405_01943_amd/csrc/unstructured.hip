@@ -14,6 +14,7 @@
 // composite is >= T.  When the key digits alone already isolate exactly the
 // wanted number of positions the index passes are skipped.
 #include "select.h"
+#include "unstructured_tiled.h"
 
 #include <mutex>
 #include <type_traits>
@@ -244,12 +245,14 @@ constexpr int kRowPhases = kUBlock / kSlabSlots;
 template <int DT, bool NORM_ROWS>
 __global__ __launch_bounds__(kUBlock) void unstructured_rows_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ f,
-    uint32_t n_keep, uint8_t *__restrict__ mask)
+    uint32_t n_keep, uint8_t *__restrict__ mask, const uint32_t *__restrict__ gate)
 {
     constexpr int NW = words_for<DT>(8);
     constexpr int NV = NW / 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     __shared__ uint32_t hist[kSlabCols][256];
+    if (gate && *gate == 0)
+        return;   // the launches before this one have done the work (uniform)
     __shared__ SelectState st[kSlabCols];
     __shared__ uint32_t any_open;
 
@@ -441,6 +444,7 @@ constexpr int kLrLines = 8;
 constexpr int kLrPasses = 8;
 constexpr int kLrThreads = 1024;
 constexpr int kLrVecs = 16;   // 16-byte vectors held by a thread
+constexpr size_t kFlagBytes = 256;   // the block of the workspace that holds the flag word of the tiled passes
 constexpr int kLrTies = 64;   // scores of the threshold's bin that are listed and ranked directly, per line
 
 struct LrState {
@@ -552,9 +556,12 @@ enum { kLrDown = 0, kLrGate = 1 };
 template <int DT, int LAYOUT, bool FACTOR_ALONG>
 __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
-    int fmode, uint32_t n_keep, uint8_t *__restrict__ mask, int vpl_log2, int lines_per_block)
+    int fmode, uint32_t n_keep, uint8_t *__restrict__ mask, int vpl_log2, int lines_per_block,
+    const uint32_t *__restrict__ gate)
 {
     constexpr int NT = kLrThreads, VPT = kLrVecs;
+    if (gate && *gate == 0)
+        return;   // the launches before this one have done the work (uniform)
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     constexpr int VR = 8 / EPV;
@@ -1077,8 +1084,10 @@ __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
 template <int DT>
 __global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__ srcv, int64_t rows, int64_t cols,
                                                         int64_t ld, void *__restrict__ dstv, int64_t ldd,
-                                                        uint32_t tiles_c)
+                                                        uint32_t tiles_c, const uint32_t *__restrict__ gate)
 {
+    if (gate && *gate == 0)
+        return;   // the launches before this one have done the work (uniform)
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     constexpr int TS = 64, VPR = TS / EPV;
@@ -1152,18 +1161,19 @@ static ResidentPlan plan_resident(int64_t rows, int64_t cols, int64_t ld, int dt
 }
 
 static dass_status launch_resident(const char *fn, const ResidentPlan &p, void *W, int64_t rows, int64_t cols,
-                                   int64_t ld, int dt, const float *norms, bool gate, bool along, int fmode,
-                                   uint32_t n_keep, uint8_t *mask_out, hipStream_t stream)
+                                   int64_t ld, int dt, const float *norms, bool col_lines, bool along, int fmode,
+                                   uint32_t n_keep, uint8_t *mask_out, const uint32_t *gate, hipStream_t stream)
 {
-    using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int, int);
+    using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int, int,
+                         const uint32_t *);
     k_t k;
     if (dt == DASS_BF16)
-        k = gate ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
+        k = col_lines ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
                           : unstructured_resident_kernel<DASS_BF16, kLrGate, false>)
                  : (along ? unstructured_resident_kernel<DASS_BF16, kLrDown, true>
                           : unstructured_resident_kernel<DASS_BF16, kLrDown, false>);
     else
-        k = gate ? (along ? unstructured_resident_kernel<DASS_F32, kLrGate, true>
+        k = col_lines ? (along ? unstructured_resident_kernel<DASS_F32, kLrGate, true>
                           : unstructured_resident_kernel<DASS_F32, kLrGate, false>)
                  : (along ? unstructured_resident_kernel<DASS_F32, kLrDown, true>
                           : unstructured_resident_kernel<DASS_F32, kLrDown, false>);
@@ -1171,7 +1181,7 @@ static dass_status launch_resident(const char *fn, const ResidentPlan &p, void *
                             (int)p.smem) != hipSuccess)
         return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, p.smem);
     hipLaunchKernelGGL(k, dim3((unsigned)p.grid), dim3(kLrThreads), p.smem, stream, W, rows, cols, ld, norms, fmode,
-                       n_keep, mask_out, p.vpl_log2, p.lpb);
+                       n_keep, mask_out, p.vpl_log2, p.lpb, gate);
     return check_launch("unstructured kernel");
 }
 
@@ -1193,14 +1203,19 @@ extern "C" size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, 
     const int64_t n = norm_axis == DASS_AXIS_ROWS ? rows : cols;
     if (n <= 0 || rows <= 0 || cols <= 0)
         return 0;
-    size_t bytes = round_up((size_t)n * sizeof(float), 256);
-    // long column lines are selected on a transposed copy of the matrix
+    // the factor vector, one flag word (in a block of its own), then room that the column-line paths share:
+    size_t bytes = round_up((size_t)n * sizeof(float), 256) + kFlagBytes, extra = 0;
     if (valid_dtype(dt) && group_axis == DASS_AXIS_ROWS && cols % 8 == 0) {
         const bool along = norm_axis == group_axis;
+        // long column lines are selected on a transposed copy of the matrix
         if (!plan_resident(rows, cols, cols, dt, true, along).fits && plan_transposed(rows, cols, dt, along).fits)
-            bytes += (size_t)rows * (size_t)cols * elem_bytes(dt);
+            extra = (size_t)rows * (size_t)cols * elem_bytes(dt);
+        // the streaming passes over 64-column tiles keep their counts and lists there
+        const TiledPlan tp = along ? plan_tiled(rows, cols, cols, dt) : TiledPlan{};
+        if (tp.fits && tp.bytes > extra)
+            extra = tp.bytes;
     }
-    return bytes;
+    return bytes + extra;
 }
 
 namespace dass {
@@ -1233,36 +1248,59 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const uint32_t n_keep = (uint32_t)(len - n_prune);
     const bool bf16 = dt == DASS_BF16;
+    const size_t f_bytes = round_up((size_t)(norm_axis == DASS_AXIS_ROWS ? rows : cols) * sizeof(float), 256);
+    // room behind the factor vector and the flag word, if the caller's workspace has it
+    char *const region = static_cast<char *>(workspace) + f_bytes + kFlagBytes;
+    const size_t region_bytes = workspace_bytes > f_bytes + kFlagBytes ? workspace_bytes - f_bytes - kFlagBytes : 0;
+    const uint32_t *gate = nullptr;   // set: the launches below run only if the word it points to is nonzero
+
+    // Column lines in the DaSS configuration (the factor varies along the line, exponent 0.5 or 1):
+    // streaming passes over 64-column tiles.  They decide every ordinary matrix; for what they do
+    // not decide they leave W untouched and set the flag, and the launches below, which then run
+    // behind that flag, redo the matrix.
+    if ((alpha == 0.5 || alpha == 1.0) && group_axis == DASS_AXIS_ROWS && norm_axis == DASS_AXIS_ROWS && n_keep > 0 &&
+        n_keep < (uint32_t)len) {
+        const TiledPlan tp = plan_tiled(rows, cols, ld, dt, mask_out);
+        if (tp.fits && region_bytes >= tp.bytes) {
+            uint32_t *flag = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + f_bytes);
+            s = launch_tiled(fn, tp, W, rows, cols, ld, dt, norms, alpha == 1.0 ? kFactorNorm : kFactorSqrt, n_keep,
+                             mask_out, flag, region, stream);
+            if (s != DASS_OK)
+                return s;
+            gate = flag;
+        }
+    }
 
     // Lines that fit the registers of one workgroup, exponent with an exact f32 factor: the
     // weights are read once.
     if ((alpha == 0.0 || alpha == 0.5 || alpha == 1.0) && len <= 0xFFFF && n_keep > 0 && n_keep < (uint32_t)len) {
         const int fmode = alpha == 0.0 ? kFactorOne : alpha == 1.0 ? kFactorNorm : kFactorSqrt;
         const bool along = norm_axis == group_axis;
-        const bool gate = group_axis == DASS_AXIS_ROWS;
-        const ResidentPlan p = plan_resident(rows, cols, ld, dt, gate, along);
+        const bool col_lines = group_axis == DASS_AXIS_ROWS;
+        const ResidentPlan p = plan_resident(rows, cols, ld, dt, col_lines, along);
         if (p.fits)
-            return launch_resident(fn, p, W, rows, cols, ld, dt, norms, gate, along, fmode, n_keep, mask_out, stream);
+            return launch_resident(fn, p, W, rows, cols, ld, dt, norms, col_lines, along, fmode, n_keep, mask_out, gate,
+                                   stream);
         // Longer column lines: transpose into the workspace, select there along the rows, transpose
         // back.  (No mask in this form: its bits would come out transposed.)
-        const ResidentPlan pt = gate && !mask_out ? plan_transposed(rows, cols, dt, along) : ResidentPlan{false, 0, 0, 0, 0};
-        const size_t f_bytes = round_up((size_t)(norm_axis == DASS_AXIS_ROWS ? rows : cols) * sizeof(float), 256);
-        if (pt.fits && workspace_bytes >= f_bytes + (size_t)rows * cols * elem_bytes(dt)) {
-            void *Wt = static_cast<char *>(workspace) + f_bytes;
+        const ResidentPlan pt =
+            col_lines && !mask_out ? plan_transposed(rows, cols, dt, along) : ResidentPlan{false, 0, 0, 0, 0};
+        if (pt.fits && region_bytes >= (size_t)rows * cols * elem_bytes(dt)) {
+            void *Wt = region;
             const int64_t tiles_r = (rows + 63) / 64, tiles_c = (cols + 63) / 64;
             if (tiles_r * tiles_c > 0x7fffffffLL)
                 return fail(DASS_ERR_SHAPE, "%s: too many tiles for one launch", fn);
             auto tk = bf16 ? transpose_kernel<DASS_BF16> : transpose_kernel<DASS_F32>;
             hipLaunchKernelGGL(tk, dim3((unsigned)(tiles_r * tiles_c)), dim3(256), 0, stream, (const void *)W, rows,
-                               cols, ld, Wt, rows, (uint32_t)tiles_c);
+                               cols, ld, Wt, rows, (uint32_t)tiles_c, gate);
             s = check_launch("transpose kernel");
             if (s != DASS_OK)
                 return s;
-            s = launch_resident(fn, pt, Wt, cols, rows, rows, dt, norms, false, along, fmode, n_keep, nullptr, stream);
+            s = launch_resident(fn, pt, Wt, cols, rows, rows, dt, norms, false, along, fmode, n_keep, nullptr, gate, stream);
             if (s != DASS_OK)
                 return s;
             hipLaunchKernelGGL(tk, dim3((unsigned)(tiles_r * tiles_c)), dim3(256), 0, stream, (const void *)Wt, cols,
-                               rows, rows, W, ld, (uint32_t)tiles_r);
+                               rows, rows, W, ld, (uint32_t)tiles_r, gate);
             return check_launch("transpose kernel");
         }
     }
@@ -1279,14 +1317,14 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
                       : (norm_axis == DASS_AXIS_COLS ? unstructured_cols_kernel<DASS_F32, true>
                                                      : unstructured_cols_kernel<DASS_F32, false>);
         hipLaunchKernelGGL(k, grid, block, 0, stream, W, rows, cols, ld, (const float *)f, n_keep,
-                           mask_out);
+                           mask_out);   // row lines: never behind the flag
     } else {
         auto k = bf16 ? (norm_axis == DASS_AXIS_ROWS ? unstructured_rows_kernel<DASS_BF16, true>
                                                      : unstructured_rows_kernel<DASS_BF16, false>)
                       : (norm_axis == DASS_AXIS_ROWS ? unstructured_rows_kernel<DASS_F32, true>
                                                      : unstructured_rows_kernel<DASS_F32, false>);
         hipLaunchKernelGGL(k, grid, block, 0, stream, W, rows, cols, ld, (const float *)f, n_keep,
-                           mask_out);
+                           mask_out, gate);
     }
     return check_launch("unstructured kernel");
 }

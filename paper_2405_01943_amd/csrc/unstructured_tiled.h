@@ -1,0 +1,34 @@
+// Unstructured selection along column lines by streaming passes over 64-column tiles
+// (unstructured_tiled.hip); called from the entry points in unstructured.hip.
+#pragma once
+
+#include "dass_internal.h"
+
+namespace dass {
+
+// Where the passes keep their intermediate results, as byte offsets into one region of the
+// caller's workspace, and the launch shape.  fits = false: the matrix does not take this path.
+struct TiledPlan {
+    bool fits;
+    int slabs;           // row slabs a column group is cut into (one workgroup each)
+    int64_t slab_rows;   // rows per slab
+    int64_t groups;      // groups of 64 columns
+    size_t off_fs, off_win, off_part, off_sel, off_cnt, off_list;
+    size_t bytes;        // size of the region
+};
+
+// Column lines of W [rows, cols] with the factor varying along the line, exponent 0.5 or 1.
+// mask_out: NULL, or where the keep bits go; a mask that is not made of whole aligned 32-bit words
+// does not take this path (its bits are corrected with 32-bit atomics).
+TiledPlan plan_tiled(int64_t rows, int64_t cols, int64_t ld, int dt, const uint8_t *mask_out = nullptr);
+
+// Enqueue the passes.  `flag` (one device word, 4-byte aligned, outside `region`) is cleared by
+// the first kernel and set by any later one that meets a case the passes do not decide (a factor
+// or product outside the range of the two-term f32 score, a threshold outside the sampled window,
+// more equal leading terms at the threshold than a list holds).  When it is set, W has not been
+// written: the caller's next launches, gated on the flag, redo the whole matrix.
+dass_status launch_tiled(const char *fn, const TiledPlan &p, void *W, int64_t rows, int64_t cols, int64_t ld, int dt,
+                         const float *norms, int fmode, uint32_t n_keep, uint8_t *mask_out, uint32_t *flag,
+                         void *region, hipStream_t stream);
+
+}  // namespace dass

@@ -271,6 +271,108 @@ def test_unstructured_threshold_among_zero_scores(gpu_device, dtype, axes):
         assert np.array_equal(mask.cpu().numpy(), want_mask)
 
 
+def _tiled_flag(workspace, n_norms):
+    """The word by which the streaming column-line passes report that they left the matrix to the
+    other kernels: it sits behind the factor vector in the workspace (the library's own layout,
+    looked at here only to tell which kernels produced the result)."""
+    off = (n_norms * 4 + 255) // 256 * 256
+    return int(workspace[off:off + 4].view(torch.int32).item())
+
+
+@pytest.mark.parametrize("dtype,rows,cols,pad", [(torch.bfloat16, 2048, 1032, 0), (torch.bfloat16, 4100, 520, 8),
+                                                 (torch.float32, 2500, 840, 4), (torch.bfloat16, 1029, 2048, 0)])
+def test_unstructured_column_lines_by_tiles(gpu_device, dtype, rows, cols, pad):
+    """Column lines of matrices large enough for the streaming passes over 64-column tiles (window,
+    counts, list, threshold, apply): ragged last tile, ragged row slabs, a leading dimension, both
+    exponents, quotas from a tenth to nine tenths and one from either end; mask bits as well."""
+    g = torch.Generator(device="cpu").manual_seed(rows * 7 + cols)
+    W0 = (torch.randn((rows, cols), generator=g) * 0.02).to(dtype)
+    W0[:, 5] *= 40.0                                  # columns of very different scale
+    W0[:, 17] *= 0.001
+    W0[torch.rand((rows, cols), generator=g) < 0.02] = 0.0
+    nrm = synth.make_norms(rows, "cpu", 21)
+    nrm[::97] = 0.0                                   # dead neurons: their scores are 0
+    nrm = nrm.to(gpu_device)
+    ws = torch.zeros(dass.unstructured_workspace_bytes(rows, cols, dtype, "rows", "rows"), dtype=torch.uint8,
+                     device=gpu_device)
+    for alpha, n_prune in ((0.5, rows // 2), (1.0, rows // 10), (0.5, rows * 9 // 10), (1.0, rows - 1), (0.5, 1)):
+        W = W0.to(gpu_device)
+        if pad:
+            W = padded(W, pad)
+        want, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), "rows", "rows", alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.full((rows, cols // 8), 0x55, dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(W, nrm, "rows", "rows", alpha, n_prune, mask_out=mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert bits_equal(W, want), f"alpha={alpha} n_prune={n_prune}: {first_mismatch(W, want)}"
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+        if pad:
+            assert torch.all(W._base[:, cols:] == 7.0)
+        if n_prune == rows // 2:
+            assert _tiled_flag(ws, rows) == 0, f"alpha={alpha} n_prune={n_prune}: an ordinary matrix must be decided " \
+                                               f"by the streaming passes (flag {_tiled_flag(ws, rows)})"
+
+
+def test_unstructured_column_lines_by_tiles_undecided_cases(gpu_device):
+    """What the streaming passes cannot decide is left to the other kernels, and the result is the
+    oracle's all the same: thousands of equal scores at the threshold (more than a list holds), a
+    product that overflows f32, a factor below the range of the two-term score."""
+    rows, cols = 2048, 1024
+    g = torch.Generator(device="cpu").manual_seed(5)
+    ws = torch.zeros(dass.unstructured_workspace_bytes(rows, cols, torch.bfloat16, "rows", "rows"), dtype=torch.uint8,
+                     device=gpu_device)
+
+    def check(W, nrm, alpha, n_prune, what):
+        want, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), "rows", "rows", alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(W, nrm, "rows", "rows", alpha, n_prune, mask_out=mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert bits_equal(W, want), f"{what}: {first_mismatch(W, want)}"
+        assert np.array_equal(mask.cpu().numpy(), want_mask), what
+        assert _tiled_flag(ws, rows) != 0, f"{what}: expected the other kernels to take over"
+
+    check(_weights(rows, cols, torch.bfloat16, gpu_device, 31, ties=True), _norms(rows, gpu_device, 31, ties=True), 1.0,
+          rows // 2, "equal scores")
+    W = (torch.randn((rows, cols), generator=g) * 0.02).to(torch.bfloat16)
+    big = W.clone()
+    big[7, :] = 3.0e38
+    nrm = synth.make_norms(rows, "cpu", 2)
+    nrm[7] = 1.0e30
+    check(big.to(gpu_device), nrm.to(gpu_device), 1.0, rows // 2, "overflowing product")
+    nrm = synth.make_norms(rows, "cpu", 3)
+    nrm[100] = 1.0e-30
+    check(W.to(gpu_device), nrm.to(gpu_device), 1.0, rows // 2, "tiny factor")
+    # and the same workspace decides an ordinary matrix again afterwards
+    W2 = W.to(gpu_device)
+    nrm = synth.make_norms(rows, "cpu", 4).to(gpu_device)
+    want, _ = oracle.mask_unstructured(to_np32(W2), nrm.cpu().numpy(), "rows", "rows", 0.5, rows // 2)
+    dass.score_mask_unstructured(W2, nrm, "rows", "rows", 0.5, rows // 2, workspace=ws)
+    torch.cuda.synchronize()
+    assert bits_equal(W2, want), first_mismatch(W2, want)
+    assert _tiled_flag(ws, rows) == 0
+
+
+def test_unstructured_column_lines_by_tiles_clustered_scores(gpu_device):
+    """Scores that no sample of rows represents (the large ones all in one block of rows) and a
+    threshold inside a cluster of leading terms that differ in their last bits: the window may
+    miss, the lists may run long; either way the result is exact."""
+    rows, cols = 4096, 512
+    g = torch.Generator(device="cpu").manual_seed(77)
+    W = torch.rand((rows, cols), generator=g) * 0.01
+    W[1000:1900] = 1.0 + torch.rand((900, cols), generator=g)           # one block of rows holds every large score
+    steps = torch.randint(0, 60, (200, cols), generator=g)
+    W[3000:3200] = (torch.full((200, cols), 0x3F000000, dtype=torch.int64) + steps).to(torch.int32).view(torch.float32)
+    W = (W * torch.where(torch.rand(W.shape, generator=g) < 0.5, -1.0, 1.0)).to(gpu_device)
+    nrm = torch.ones(rows, device=gpu_device)
+    for n_prune in (rows - 900 - 100, rows - 900 - 3, rows - 450, rows // 2):
+        Wc = W.clone()
+        want, _ = oracle.mask_unstructured(to_np32(Wc), nrm.cpu().numpy(), "rows", "rows", 1.0, n_prune)
+        dass.score_mask_unstructured(Wc, nrm, "rows", "rows", 1.0, n_prune)
+        torch.cuda.synchronize()
+        assert bits_equal(Wc, want), f"n_prune={n_prune}: {first_mismatch(Wc, want)}"
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
