@@ -316,13 +316,13 @@ __global__ __launch_bounds__(256) void scan_kernel(const uint16_t *__restrict__ 
 // ------------------------------------------------------------------- apply --
 // Nothing is shared between rows here, so the matrix is covered by many small workgroups whose
 // threads make one trip each (streams faster than resident workgroups that loop): 256 threads take
-// 4 row blocks of a tile, a thread one 16-byte vector of each.  A score inside its column's bin
+// 8 row blocks of a tile, a thread one 16-byte vector of each.  A score inside its column's bin
 // is rare (a few dozen per column): the workgroup gathers them in LDS (up to kLocal per column)
 // and moves them to the columns' lists at the end, one global counter update per column; what
 // does not fit goes to the list directly.
-constexpr int kApplyThreads = 256, kApplyTrips = 4, kLocal = 6;
+constexpr int kApplyThreads = 256, kApplyTrips = 8, kLocal = 8;
 
-template <int DT>
+template <int DT, bool MASK>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__ Wv, uint32_t rows, uint32_t cols,
                                                               int64_t ld, const float *__restrict__ fs,
                                                               const Select *__restrict__ sel, uint32_t groups,
@@ -335,9 +335,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__
     __shared__ uint32_t found[kCols];
     __shared__ uint32_t base[kCols];
     __shared__ uint32_t held[kCols][kLocal][3];
+    __shared__ uint2 bins[kCols];   // (lo, width) of the tile's columns
     const uint32_t stop = *flag;
     const int tid = threadIdx.x;
     const uint32_t g = blockIdx.x % groups, block = blockIdx.x / groups;
+    if (tid < kCols) {
+        const Select t = g * kCols + tid < cols ? sel[g * kCols + tid] : Select{0, 0, 0, 0};
+        bins[tid] = make_uint2(t.lo, t.width);
+        found[tid] = 0;
+    }
     const uint32_t piece = tid % LPR, r0 = block * (U * RPI) + tid / LPR;
     const uint32_t c0 = g * kCols + piece * EPV;
     const bool active = c0 < cols;
@@ -352,61 +358,79 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__
             f[u] = fs[ru];
         }
     }
+    if (stop)
+        return;   // the matrix is left as it was for the gated launches that follow (uniform)
+    __syncthreads();
     uint32_t lo[EPV], width[EPV];
 #pragma unroll
     for (int e = 0; e < EPV; ++e) {
-        const Select t = active ? sel[c0 + e] : Select{0, 0, 0, 0};
-        lo[e] = t.lo;
-        width[e] = t.width;
+        const uint2 t = bins[piece * EPV + e];
+        lo[e] = t.x;
+        width[e] = t.y;
     }
-    if (stop)
-        return;   // the matrix is left as it was for the gated launches that follow (uniform)
-    if (tid < kCols)
-        found[tid] = 0;
-    __syncthreads();
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t ru = r0 + u * RPI;
         const bool live = active && ru < rows;
         uint32_t kept = 0;
         if (live) {
-            uint32_t hits = 0;
+            // d = bits(p) - lo is negative (both are below 2^31) exactly for a pruned weight; its sign,
+            // spread over the word, is the mask that clears the weight.  Whether any of the vector's scores
+            // lies inside its column's bin is one flag per lane; which ones is asked only then.
+            uint32_t d[EPV];
+            int32_t gone[EPV];
+            bool hit = false;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                const uint32_t a = __float_as_uint(fabsf(elem_of<DT>(x[u], e)) * f[u]);
-                const bool keep = a >= lo[e];
-                hits |= (a - lo[e] < width[e] ? 1u : 0u) << e;
-                kept |= (keep ? 1u : 0u) << e;
+                d[e] = __float_as_uint(fabsf(elem_of<DT>(x[u], e)) * f[u]) - lo[e];
+                hit |= d[e] < width[e];
+                gone[e] = (int32_t)d[e] >> 31;
+                if constexpr (MASK)
+                    kept |= (uint32_t)(~gone[e] & 1) << e;
             }
-            while (hits) {   // rarely entered
-                const int e = __ffs((int)hits) - 1;
-                hits &= hits - 1;
-                float w = 0.0f;
+            if (hit) {   // rarely entered
+                uint32_t hits = 0;
 #pragma unroll
-                for (int k = 0; k < EPV; ++k)
-                    w = k == e ? fabsf(elem_of<DT>(x[u], k)) : w;
-                const float p = w * f[u];
-                const uint32_t a = __float_as_uint(p), b = mono(fmaf(w, f[u], -p)), c = 0xFFFFu - ru;
-                const uint32_t col = piece * EPV + e;
-                const uint32_t slot = atomicAdd(&found[col], 1u);
-                if (slot < (uint32_t)kLocal) {
-                    held[col][slot][0] = a;
-                    held[col][slot][1] = b;
-                    held[col][slot][2] = c;
-                } else {   // more of them in one workgroup than it holds: straight to the list
-                    const uint32_t at = atomicAdd(cnt + g * kCols + col, 1u);
-                    if (at < (uint32_t)kCap)
-                        list[(size_t)(g * kCols + col) * kCap + at] = Entry{a, b, c, 0};
-                    else
-                        atomicOr(flag, kWhyList);
+                for (int e = 0; e < EPV; ++e)
+                    hits |= (d[e] < width[e] ? 1u : 0u) << e;
+                while (hits) {
+                    const int e = __ffs((int)hits) - 1;
+                    hits &= hits - 1;
+                    float w = 0.0f;
+#pragma unroll
+                    for (int k = 0; k < EPV; ++k)
+                        w = k == e ? fabsf(elem_of<DT>(x[u], k)) : w;
+                    const float p = w * f[u];
+                    const uint32_t a = __float_as_uint(p), b = mono(fmaf(w, f[u], -p)), c = 0xFFFFu - ru;
+                    const uint32_t col = piece * EPV + e;
+                    const uint32_t slot = atomicAdd(&found[col], 1u);
+                    if (slot < (uint32_t)kLocal) {
+                        held[col][slot][0] = a;
+                        held[col][slot][1] = b;
+                        held[col][slot][2] = c;
+                    } else {   // more of them in one workgroup than it holds: straight to the list
+                        const uint32_t at = atomicAdd(cnt + g * kCols + col, 1u);
+                        if (at < (uint32_t)kCap)
+                            list[(size_t)(g * kCols + col) * kCap + at] = Entry{a, b, c, 0};
+                        else
+                            atomicOr(flag, kWhyList);
+                    }
                 }
             }
+            if constexpr (DT == DASS_BF16) {
 #pragma unroll
-            for (int e = 0; e < EPV; ++e)
-                zero_lane_if<DT>(x[u], e, ((kept >> e) & 1u) == 0);
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t clear = ((uint32_t)gone[2 * k] & 0xffffu) | ((uint32_t)gone[2 * k + 1] & 0xffff0000u);
+                    x[u][k] &= ~clear;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    x[u][k] &= ~(uint32_t)gone[k];
+            }
             __builtin_nontemporal_store(x[u], reinterpret_cast<u32x4 *>(W + (int64_t)ru * ld * EB));
         }
-        if (mask) {
+        if constexpr (MASK) {
             if constexpr (EPV == 8) {
                 if (live)
                     mask[(size_t)ru * (cols / 8) + c0 / 8] = (uint8_t)kept;
@@ -456,10 +480,15 @@ __global__ __launch_bounds__(256) void fix_kernel(void *__restrict__ Wv, uint32_
         return;
     // four loads that do not wait for one another (each is a trip to memory another kernel wrote)
     const uint32_t stop = *flag;
-    const Select s = sel[c];
-    const uint32_t n = cnt[c];
+    Select s = sel[c];
+    uint32_t n = cnt[c];
     Entry mine[kCap / 64];
     mine[0] = list[(size_t)c * kCap + lane];   // past the list's end: stale or never written, not used
+    // the same for every lane of the wavefront: say so, the loops below then run on the scalar unit
+    n = __builtin_amdgcn_readfirstlane(n);
+    s.width = __builtin_amdgcn_readfirstlane(s.width);
+    s.need = __builtin_amdgcn_readfirstlane(s.need);
+    s.inside = __builtin_amdgcn_readfirstlane(s.inside);
     if (stop || s.width == 0)
         return;   // the passes have given up, or every score of the bin is kept
     if (n != s.inside) {   // ruled out by identical arithmetic in hist and apply; never trust it silently
@@ -472,7 +501,13 @@ __global__ __launch_bounds__(256) void fix_kernel(void *__restrict__ Wv, uint32_
         const uint32_t k = lane + 64 * j;
         mine[j] = k < n ? list[(size_t)c * kCap + k] : Entry{0, 0, 0, 0};
     }
-    uint32_t above[kCap / 64] = {0, 0, 0, 0};
+    // Ranking on (A, B) as one 64-bit number; C (the row) is looked at only where two entries agree in
+    // both, which a second sweep settles if it happens at all.
+    uint64_t key[kCap / 64];
+#pragma unroll
+    for (int j = 0; j < kCap / 64; ++j)
+        key[j] = (uint64_t)mine[j].a << 32 | mine[j].b;
+    uint32_t above[kCap / 64] = {0, 0, 0, 0}, same[kCap / 64] = {0, 0, 0, 0};
     const int slots = (int)((n + 63) / 64);   // uniform: 1 for an ordinary column
 #pragma unroll
     for (int src = 0; src < kCap / 64; ++src) {
@@ -480,13 +515,35 @@ __global__ __launch_bounds__(256) void fix_kernel(void *__restrict__ Wv, uint32_
             break;
         const int in_slot = (int)n - 64 * src < 64 ? (int)n - 64 * src : 64;
         for (int k = 0; k < in_slot; ++k) {
-            const uint32_t oa = (uint32_t)__builtin_amdgcn_readlane((int)mine[src].a, k),
-                           ob = (uint32_t)__builtin_amdgcn_readlane((int)mine[src].b, k),
-                           oc = (uint32_t)__builtin_amdgcn_readlane((int)mine[src].c, k);
+            const uint64_t o = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine[src].a, k) << 32 |
+                               (uint32_t)__builtin_amdgcn_readlane((int)mine[src].b, k);
 #pragma unroll
             for (int j = 0; j < kCap / 64; ++j)
-                if (j < slots)
-                    above[j] += (oa > mine[j].a) | ((oa == mine[j].a) & ((ob > mine[j].b) | ((ob == mine[j].b) & (oc > mine[j].c))));
+                if (j < slots) {
+                    above[j] += o > key[j];
+                    same[j] += o == key[j];
+                }
+        }
+    }
+    bool tied = false;   // an entry counts itself once
+#pragma unroll
+    for (int j = 0; j < kCap / 64; ++j)
+        tied |= lane + 64 * j < n && same[j] > 1;
+    if (__ballot(tied)) {
+#pragma unroll
+        for (int src = 0; src < kCap / 64; ++src) {
+            if (src >= slots)
+                break;
+            const int in_slot = (int)n - 64 * src < 64 ? (int)n - 64 * src : 64;
+            for (int k = 0; k < in_slot; ++k) {
+                const uint64_t o = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine[src].a, k) << 32 |
+                                   (uint32_t)__builtin_amdgcn_readlane((int)mine[src].b, k);
+                const uint32_t oc = (uint32_t)__builtin_amdgcn_readlane((int)mine[src].c, k);
+#pragma unroll
+                for (int j = 0; j < kCap / 64; ++j)
+                    if (j < slots)
+                        above[j] += (o == key[j]) & (oc > mine[j].c);
+            }
         }
     }
     char *W = static_cast<char *>(Wv);
@@ -578,9 +635,10 @@ dass_status launch_tiled(const char *fn, const TiledPlan &p, void *W, int64_t ro
     hipLaunchKernelGGL(scan_kernel, per_col, dim3(256), 0, stream, (const uint16_t *)part, (const Window *)win, c32, groups,
                        slabs, n_keep, sel, flag);
     const uint32_t rows_per_block = kApplyTrips * kApplyThreads / (bf16 ? 8 : 16);
-    hipLaunchKernelGGL(bf16 ? apply_kernel<DASS_BF16> : apply_kernel<DASS_F32>,
-                       dim3(groups * ((r32 + rows_per_block - 1) / rows_per_block)), dim3(kApplyThreads), 0, stream, W, r32,
-                       c32, ld, (const float *)fs, (const Select *)sel, groups, cnt, list, mask_out, flag);
+    auto ak = bf16 ? (mask_out ? apply_kernel<DASS_BF16, true> : apply_kernel<DASS_BF16, false>)
+                   : (mask_out ? apply_kernel<DASS_F32, true> : apply_kernel<DASS_F32, false>);
+    hipLaunchKernelGGL(ak, dim3(groups * ((r32 + rows_per_block - 1) / rows_per_block)), dim3(kApplyThreads), 0, stream, W,
+                       r32, c32, ld, (const float *)fs, (const Select *)sel, groups, cnt, list, mask_out, flag);
     hipLaunchKernelGGL(bf16 ? fix_kernel<DASS_BF16> : fix_kernel<DASS_F32>, per_col, dim3(256), 0, stream, W, c32, ld,
                        (const Select *)sel, (const uint32_t *)cnt, (const Entry *)list, mask_out, flag);
     return check_launch("tiled unstructured kernels");
