@@ -208,10 +208,13 @@ dass_status dass_input_norms(const void *X, int64_t T, int64_t ldx, int64_t d, d
  * converts a sparsity ratio s to n_prune = floor(s * line length).
  *
  *   workspace  device scratch of at least dass_unstructured_workspace_bytes()
- *              bytes, 16-byte aligned (holds f and the per-line selection state;
- *              for column lines of more than 16384 bf16 / 8192 f32 weights also a
- *              transposed copy of W, rows * cols elements, on which such lines
- *              are selected).
+ *              bytes, 16-byte aligned.  It holds f; for column lines
+ *              (group_axis = ROWS) of a large matrix also the counts and short
+ *              lists of the passes that select them tile by tile (a few tens
+ *              of MB for a 7B-sized matrix), or, where those passes do not
+ *              apply and a line has more than 16384 bf16 / 8192 f32 weights,
+ *              a transposed copy of W (rows * cols elements) on which such
+ *              lines are selected.  Its contents after the call are unspecified.
  */
 size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, dass_dtype dt,
                                          dass_axis norm_axis, dass_axis group_axis);
