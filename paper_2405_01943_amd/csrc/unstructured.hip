@@ -94,13 +94,15 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t need, ui
 template <int DT, bool NORM_COLS>
 __global__ __launch_bounds__(kUBlock) void unstructured_cols_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ f,
-    uint32_t n_keep, uint8_t *__restrict__ mask)
+    uint32_t n_keep, uint8_t *__restrict__ mask, const uint32_t *__restrict__ gate, uint32_t gate_rows)
 {
     constexpr int NW = words_for<DT>(8);
     constexpr int NV = NW / 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     __shared__ uint32_t hist[256];
     __shared__ SelectState st;
+    if (gate && gate[blockIdx.x / gate_rows] == 0)
+        return;   // the launch before this one has done this row (uniform)
 
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x;
@@ -557,11 +559,13 @@ template <int DT, int LAYOUT, bool FACTOR_ALONG>
 __global__ __launch_bounds__(kLrThreads) void unstructured_resident_kernel(
     void *__restrict__ Wv, int64_t rows, int64_t cols, int64_t ld, const float *__restrict__ norms,
     int fmode, uint32_t n_keep, uint8_t *__restrict__ mask, int vpl_log2, int lines_per_block,
-    const uint32_t *__restrict__ gate)
+    const uint32_t *__restrict__ gate, uint32_t gate_rows)
 {
     constexpr int NT = kLrThreads, VPT = kLrVecs;
-    if (gate && *gate == 0)
-        return;   // the launches before this one have done the work (uniform)
+    // gate: the launches before this one set a word where they left work - one for the whole matrix
+    // (gate_rows = 0) or one per block of gate_rows rows (row lines)
+    if (gate && gate[gate_rows ? (uint32_t)(((int64_t)blockIdx.x * lines_per_block) / gate_rows) : 0u] == 0)
+        return;   // uniform
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     constexpr int VR = 8 / EPV;
@@ -1162,10 +1166,11 @@ static ResidentPlan plan_resident(int64_t rows, int64_t cols, int64_t ld, int dt
 
 static dass_status launch_resident(const char *fn, const ResidentPlan &p, void *W, int64_t rows, int64_t cols,
                                    int64_t ld, int dt, const float *norms, bool col_lines, bool along, int fmode,
-                                   uint32_t n_keep, uint8_t *mask_out, const uint32_t *gate, hipStream_t stream)
+                                   uint32_t n_keep, uint8_t *mask_out, const uint32_t *gate, uint32_t gate_rows,
+                                   hipStream_t stream)
 {
     using k_t = void (*)(void *, int64_t, int64_t, int64_t, const float *, int, uint32_t, uint8_t *, int, int,
-                         const uint32_t *);
+                         const uint32_t *, uint32_t);
     k_t k;
     if (dt == DASS_BF16)
         k = col_lines ? (along ? unstructured_resident_kernel<DASS_BF16, kLrGate, true>
@@ -1181,7 +1186,7 @@ static dass_status launch_resident(const char *fn, const ResidentPlan &p, void *
                             (int)p.smem) != hipSuccess)
         return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, p.smem);
     hipLaunchKernelGGL(k, dim3((unsigned)p.grid), dim3(kLrThreads), p.smem, stream, W, rows, cols, ld, norms, fmode,
-                       n_keep, mask_out, p.vpl_log2, p.lpb, gate);
+                       n_keep, mask_out, p.vpl_log2, p.lpb, gate, gate_rows);
     return check_launch("unstructured kernel");
 }
 
@@ -1214,6 +1219,11 @@ extern "C" size_t dass_unstructured_workspace_bytes(int64_t rows, int64_t cols, 
         const TiledPlan tp = along ? plan_tiled(rows, cols, cols, dt) : TiledPlan{};
         if (tp.fits && tp.bytes > extra)
             extra = tp.bytes;
+    }
+    if (valid_dtype(dt) && group_axis == DASS_AXIS_COLS && norm_axis == DASS_AXIS_COLS && cols % 8 == 0) {
+        const RowlinesPlan rp = plan_rowlines(rows, cols, cols, dt);   // one word per block of rows
+        if (rp.fits)
+            extra = rp.todo_bytes;
     }
     return bytes + extra;
 }
@@ -1252,7 +1262,8 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
     // room behind the factor vector and the flag word, if the caller's workspace has it
     char *const region = static_cast<char *>(workspace) + f_bytes + kFlagBytes;
     const size_t region_bytes = workspace_bytes > f_bytes + kFlagBytes ? workspace_bytes - f_bytes - kFlagBytes : 0;
-    const uint32_t *gate = nullptr;   // set: the launches below run only if the word it points to is nonzero
+    const uint32_t *gate = nullptr;   // set: the launches below run only where the word(s) it points to are nonzero
+    uint32_t gate_rows = 0;           // 0: one word for the whole matrix; else one word per block of so many rows
 
     // Column lines in the DaSS configuration (the factor varies along the line, exponent 0.5 or 1):
     // streaming passes over 64-column tiles.  They decide every ordinary matrix; for what they do
@@ -1270,6 +1281,21 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
             gate = flag;
         }
     }
+    // Row lines in the DaSS configuration: one launch in which a workgroup owns 8 whole rows; blocks of
+    // rows it does not decide are marked and redone by the launches below.
+    if ((alpha == 0.5 || alpha == 1.0) && group_axis == DASS_AXIS_COLS && norm_axis == DASS_AXIS_COLS && n_keep > 0 &&
+        n_keep < (uint32_t)len) {
+        const RowlinesPlan rp = plan_rowlines(rows, cols, ld, dt, mask_out);
+        if (rp.fits && region_bytes >= rp.todo_bytes) {
+            uint32_t *todo = reinterpret_cast<uint32_t *>(region);
+            s = launch_rowlines(fn, rp, W, rows, cols, ld, dt, norms, alpha == 1.0 ? kFactorNorm : kFactorSqrt, n_keep,
+                                mask_out, todo, stream);
+            if (s != DASS_OK)
+                return s;
+            gate = todo;
+            gate_rows = kRowlinesBlock;
+        }
+    }
 
     // Lines that fit the registers of one workgroup, exponent with an exact f32 factor: the
     // weights are read once.
@@ -1280,7 +1306,7 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
         const ResidentPlan p = plan_resident(rows, cols, ld, dt, col_lines, along);
         if (p.fits)
             return launch_resident(fn, p, W, rows, cols, ld, dt, norms, col_lines, along, fmode, n_keep, mask_out, gate,
-                                   stream);
+                                   gate_rows, stream);
         // Longer column lines: transpose into the workspace, select there along the rows, transpose
         // back.  (No mask in this form: its bits would come out transposed.)
         const ResidentPlan pt =
@@ -1296,7 +1322,7 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
             s = check_launch("transpose kernel");
             if (s != DASS_OK)
                 return s;
-            s = launch_resident(fn, pt, Wt, cols, rows, rows, dt, norms, false, along, fmode, n_keep, nullptr, gate, stream);
+            s = launch_resident(fn, pt, Wt, cols, rows, rows, dt, norms, false, along, fmode, n_keep, nullptr, gate, 0, stream);
             if (s != DASS_OK)
                 return s;
             hipLaunchKernelGGL(tk, dim3((unsigned)(tiles_r * tiles_c)), dim3(256), 0, stream, (const void *)Wt, cols,
@@ -1317,7 +1343,7 @@ static dass_status score_mask_unstructured_impl(const char *fn, void *W, int64_t
                       : (norm_axis == DASS_AXIS_COLS ? unstructured_cols_kernel<DASS_F32, true>
                                                      : unstructured_cols_kernel<DASS_F32, false>);
         hipLaunchKernelGGL(k, grid, block, 0, stream, W, rows, cols, ld, (const float *)f, n_keep,
-                           mask_out);   // row lines: never behind the flag
+                           mask_out, gate, gate_rows);
     } else {
         auto k = bf16 ? (norm_axis == DASS_AXIS_ROWS ? unstructured_rows_kernel<DASS_BF16, true>
                                                      : unstructured_rows_kernel<DASS_BF16, false>)

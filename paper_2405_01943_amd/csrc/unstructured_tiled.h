@@ -1,5 +1,6 @@
-// Unstructured selection along column lines by streaming passes over 64-column tiles
-// (unstructured_tiled.hip); called from the entry points in unstructured.hip.
+// Unstructured selection by streaming passes: column lines over 64-column tiles
+// (unstructured_tiled.hip), row lines by workgroups that own whole rows (unstructured_rows.hip);
+// called from the entry points in unstructured.hip.
 #pragma once
 
 #include "dass_internal.h"
@@ -30,5 +31,24 @@ TiledPlan plan_tiled(int64_t rows, int64_t cols, int64_t ld, int dt, const uint8
 dass_status launch_tiled(const char *fn, const TiledPlan &p, void *W, int64_t rows, int64_t cols, int64_t ld, int dt,
                          const float *norms, int fmode, uint32_t n_keep, uint8_t *mask_out, uint32_t *flag,
                          void *region, hipStream_t stream);
+
+// ---- row lines (unstructured_rows.hip): one launch, a workgroup owns kRowlinesBlock whole rows ----
+constexpr int kRowlinesBlock = 8;
+
+struct RowlinesPlan {
+    bool fits;
+    int64_t blocks;      // workgroups = blocks of kRowlinesBlock rows
+    size_t smem;         // dynamic LDS of the kernel
+    size_t todo_bytes;   // one word per block in the caller's workspace
+};
+
+// Row lines of W [rows, cols] with the factor varying along the line, exponent 0.5 or 1.
+RowlinesPlan plan_rowlines(int64_t rows, int64_t cols, int64_t ld, int dt, const uint8_t *mask_out = nullptr);
+
+// Enqueue the kernel.  todo[b] is written for every block b of kRowlinesBlock rows: 0 if the
+// block's rows are done, 1 if they were left for the caller's next launch, gated per block.
+dass_status launch_rowlines(const char *fn, const RowlinesPlan &p, void *W, int64_t rows, int64_t cols, int64_t ld, int dt,
+                            const float *norms, int fmode, uint32_t n_keep, uint8_t *mask_out, uint32_t *todo,
+                            hipStream_t stream);
 
 }  // namespace dass

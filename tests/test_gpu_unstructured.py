@@ -373,6 +373,86 @@ def test_unstructured_column_lines_by_tiles_clustered_scores(gpu_device):
         assert bits_equal(Wc, want), f"n_prune={n_prune}: {first_mismatch(Wc, want)}"
 
 
+def _rowline_todo(workspace, n_norms, rows):
+    """The words by which the row-line kernel reports blocks of 8 rows it left to the other kernels:
+    they follow the factor vector and one 256-byte block in the workspace (the library's own layout,
+    looked at here only to tell which kernels produced the result)."""
+    off = (n_norms * 4 + 255) // 256 * 256 + 256
+    return workspace[off:off + 4 * ((rows + 7) // 8)].view(torch.int32).cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype,rows,cols,pad", [(torch.bfloat16, 1032, 2048, 0), (torch.bfloat16, 520, 4104, 8),
+                                                 (torch.float32, 837, 2504, 4), (torch.bfloat16, 2052, 1024, 0)])
+def test_unstructured_row_lines_streamed(gpu_device, dtype, rows, cols, pad):
+    """Row lines of matrices large enough for the one-launch streaming kernel (a workgroup owns 8 whole
+    rows: window, counts, bin, apply with the bin's scores listed, ranking): a ragged last block of
+    rows, lines that are no multiple of the workgroup's stride, a leading dimension, both exponents,
+    quotas from a tenth to nine tenths and one from either end; mask bits as well."""
+    g = torch.Generator(device="cpu").manual_seed(rows * 7 + cols)
+    W0 = (torch.randn((rows, cols), generator=g) * 0.02).to(dtype)
+    W0[5, :] *= 40.0                                  # rows of very different scale
+    W0[17, :] *= 0.001
+    W0[torch.rand((rows, cols), generator=g) < 0.02] = 0.0
+    nrm = synth.make_norms(cols, "cpu", 21)
+    nrm[::97] = 0.0                                   # dead neurons: their scores are 0
+    nrm = nrm.to(gpu_device)
+    ws = torch.zeros(dass.unstructured_workspace_bytes(rows, cols, dtype, "cols", "cols"), dtype=torch.uint8,
+                     device=gpu_device)
+    for alpha, n_prune in ((1.0, cols // 2), (0.5, cols // 10), (1.0, cols * 9 // 10), (0.5, cols - 1), (1.0, 1)):
+        W = W0.to(gpu_device)
+        if pad:
+            W = padded(W, pad)
+        want, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), "cols", "cols", alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.full((rows, cols // 8), 0x55, dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(W, nrm, "cols", "cols", alpha, n_prune, mask_out=mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert bits_equal(W, want), f"alpha={alpha} n_prune={n_prune}: {first_mismatch(W, want)}"
+        assert np.array_equal(mask.cpu().numpy(), want_mask)
+        if pad:
+            assert torch.all(W._base[:, cols:] == 7.0)
+        if n_prune == cols // 2:
+            todo = _rowline_todo(ws, cols, rows)
+            assert not todo.any(), f"alpha={alpha}: ordinary rows must be decided by the streaming kernel ({todo.sum()} blocks left)"
+
+
+def test_unstructured_row_lines_streamed_undecided_cases(gpu_device):
+    """Blocks of rows that the streaming kernel cannot decide are left to the other kernels, block by
+    block, and the result is the oracle's all the same: rows of thousands of equal scores beside
+    ordinary ones, a product that overflows f32, a factor below the range of the two-term score."""
+    rows, cols = 1024, 2048
+    g = torch.Generator(device="cpu").manual_seed(5)
+    ws = torch.zeros(dass.unstructured_workspace_bytes(rows, cols, torch.bfloat16, "cols", "cols"), dtype=torch.uint8,
+                     device=gpu_device)
+
+    def check(W, nrm, alpha, n_prune, what, expect_left):
+        want, want_mask = oracle.mask_unstructured(to_np32(W), nrm.cpu().numpy(), "cols", "cols", alpha, n_prune,
+                                                   want_mask=True)
+        mask = torch.zeros((rows, cols // 8), dtype=torch.uint8, device=gpu_device)
+        dass.score_mask_unstructured(W, nrm, "cols", "cols", alpha, n_prune, mask_out=mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert bits_equal(W, want), f"{what}: {first_mismatch(W, want)}"
+        assert np.array_equal(mask.cpu().numpy(), want_mask), what
+        left = set(np.nonzero(_rowline_todo(ws, cols, rows))[0].tolist())
+        assert left == expect_left, f"{what}: blocks left {sorted(left)[:8]}.., expected {sorted(expect_left)[:8]}.."
+
+    W = (torch.randn((rows, cols), generator=g) * 0.02).to(torch.bfloat16)
+    tied = W.clone()
+    vals = torch.tensor([-0.5, 0.0, 0.25, 0.5, -0.25, 1.0])
+    for r in (40, 41, 700):                                # rows of equal scores: blocks 5 and 87
+        tied[r] = vals[torch.randint(0, len(vals), (cols,), generator=g)].to(torch.bfloat16)
+    check(tied.to(gpu_device), torch.ones(cols, device=gpu_device), 1.0, cols // 2, "equal scores", {5, 87})
+    big = W.clone()
+    big[:, 7] = 3.0e38
+    nrm = synth.make_norms(cols, "cpu", 2)
+    nrm[7] = 1.0e30
+    check(big.to(gpu_device), nrm.to(gpu_device), 1.0, cols // 2, "overflowing product", set(range(rows // 8)))
+    nrm = synth.make_norms(cols, "cpu", 3)
+    nrm[100] = 1.0e-30
+    check(W.to(gpu_device), nrm.to(gpu_device), 1.0, cols // 2, "tiny factor", set(range(rows // 8)))
+    check(W.to(gpu_device), synth.make_norms(cols, "cpu", 4).to(gpu_device), 0.5, cols // 2, "ordinary again", set())
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
