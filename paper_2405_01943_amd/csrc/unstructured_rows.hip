@@ -52,14 +52,16 @@ __device__ __forceinline__ uint32_t mono(float q)   // unsigned integer that gro
     return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
 }
 
-// Column sampled for slot k of kSamples: one per stratum, at an offset that changes from
-// stratum to stratum.
-__device__ __forceinline__ uint32_t sample_col(uint32_t k, uint32_t cols)
+// The 128 sampled positions of a row are 16 runs of 8 consecutive columns (a sample spread one by one
+// would touch 128 of the row's 172 memory lines: most of the matrix, just to sample it): run k
+// lies in the k-th sixteenth of the row, at an offset that changes from run to run.  Returns the
+// run's first column, a multiple of 8.
+constexpr int kRuns = kSamples / 8;
+__device__ __forceinline__ uint32_t sample_run(uint32_t k, uint32_t cols)
 {
-    const uint32_t stratum = cols / kSamples;
-    const uint32_t base = (uint32_t)(((uint64_t)k * cols) / kSamples);
-    const uint32_t c = base + (stratum ? ((k * 2654435761u) >> 8) % stratum : 0u);
-    return c < cols ? c : cols - 1;
+    const uint32_t octets = cols / 8, stratum = octets / kRuns;   // cols >= 1024: stratum >= 8
+    const uint32_t o = (uint32_t)(((uint64_t)k * octets) / kRuns) + ((k * 2654435761u) >> 8) % stratum;
+    return (o < octets ? o : octets - 1) * 8;
 }
 
 // Layout of the dynamic LDS, in bytes from its start.
@@ -72,10 +74,9 @@ __host__ __device__ inline Smem smem_layout(uint32_t cols)
     size_t off = 0;
     m.fs = off;
     off += ((size_t)cols * 4 + 15) / 16 * 16;
-    m.hist = off;
-    off += (size_t)kRows * kStride * 4;
-    m.list = off;
-    off += (size_t)kRows * kCap * 12;
+    // the counters are dead once the bins are found (phase C), the lists are filled after that: one place for both
+    m.hist = m.list = off;
+    off += (size_t)kRows * (kCap * 12 > kStride * 4 ? kCap * 12 : kStride * 4);
     m.cnt = off;
     off += kRows * 4;
     m.win = off;
@@ -116,18 +117,21 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
 
     // the rows' samples (phase A, one wavefront per row) are fetched first: they are on their way
     // while phase 0 runs.  Their factors come straight from the norms.
-    uint32_t smp[2] = {0, 0};
-    if ((uint32_t)wave < n_rows) {
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const uint32_t c = sample_col(lane + 64 * q, cols);
-            float w;
-            if constexpr (DT == DASS_BF16)
-                w = __uint_as_float((uint32_t) * reinterpret_cast<const uint16_t *>(W + wave * row_bytes + c * 2) << 16);
-            else
-                w = *reinterpret_cast<const float *>(W + wave * row_bytes + c * 4);
-            smp[q] = __float_as_uint(fabsf(w) * (factor_of(norms[c], fmode) * kFactorScale));
+    float smp_w[2] = {0.0f, 0.0f}, smp_n[2] = {0.0f, 0.0f};
+    if ((uint32_t)wave < n_rows) {   // lane l: columns 2 (l % 4), + 1 of run l / 4
+        const uint32_t c = sample_run(lane / 4, cols) + 2 * (lane % 4);
+        if constexpr (DT == DASS_BF16) {
+            const uint32_t two = *reinterpret_cast<const uint32_t *>(W + wave * row_bytes + c * 2);
+            smp_w[0] = __uint_as_float(two << 16);
+            smp_w[1] = __uint_as_float(two & 0xffff0000u);
+        } else {
+            const float2 two = *reinterpret_cast<const float2 *>(W + wave * row_bytes + c * 4);
+            smp_w[0] = two.x;
+            smp_w[1] = two.y;
         }
+        const float2 n2 = *reinterpret_cast<const float2 *>(norms + c);
+        smp_n[0] = n2.x;
+        smp_n[1] = n2.y;
     }
 
     // ---- 0: scaled factors of every column, counters cleared
@@ -155,7 +159,10 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
 
     // ---- A: the rows' windows, one wavefront per row
     if ((uint32_t)wave < n_rows) {
-        const uint32_t *s = smp;
+        uint32_t s[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            s[q] = __float_as_uint(fabsf(smp_w[q]) * (factor_of(smp_n[q], fmode) * kFactorScale));
         // Ranks (from the top) of the two order statistics: the wanted quantile of the sample give or
         // take six standard deviations of the sampled count above the threshold, and one more.
         const float phi = (float)n_keep / (float)cols;
