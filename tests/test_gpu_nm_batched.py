@@ -46,6 +46,26 @@ def test_batched_model_of_five_layers(gpu_device, dtype, n_keep, m):
         _check(wd, dn, nrm, ("cols", "cols"), 1.0, n_keep, m)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("n_keep,m", [(1, 2), (2, 4), (4, 8)])
+@pytest.mark.parametrize("d,d_int", [(328, 1384), (1024, 2752), (72, 136)])
+def test_batched_one_block(gpu_device, dtype, n_keep, m, d, d_int):
+    """Gate, Up and Down of one MLP block (and of two blocks) in one call, Down-Proj first: what
+    bench.py's step does; shapes ragged against every workgroup width."""
+    for n_blocks in (1, 2):
+        layers = [_layer(d, d_int, dtype, gpu_device, 300 + k) for k in range(n_blocks)]
+        work = [[w.clone() for w in (g, u, dn)] for g, u, dn, _ in layers]
+        tasks = []
+        for (g, u, dn, nrm), (wg, wu, wd) in zip(layers, work):
+            tasks += [(wd, nrm, "cols", "cols", 1.0), (wg, nrm, "rows", "rows", 0.5), (wu, nrm, "rows", "rows", 0.5)]
+        dass.score_mask_nm_batched(tasks, n_keep, m)
+        torch.cuda.synchronize()
+        for (g, u, dn, nrm), (wg, wu, wd) in zip(layers, work):
+            _check(wg, g, nrm, ("rows", "rows"), 0.5, n_keep, m)
+            _check(wu, u, nrm, ("rows", "rows"), 0.5, n_keep, m)
+            _check(wd, dn, nrm, ("cols", "cols"), 1.0, n_keep, m)
+
+
 def test_batched_more_matrices_than_one_launch_holds(gpu_device):
     """130 equal matrices: split over two launches (96 + 34); each gets its own norms."""
     rows, cols, n = 64, 136, 130
