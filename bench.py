@@ -44,10 +44,11 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; see profiles/).  A figure only stands while the source
 # of its kernel is the one the counters were taken on; otherwise `traffic` is null.
 MEASURED_TRAFFIC = {
-    "stage1": {"sources": ("calib.hip",), "sha256": "7f62b546a013a5faca604019358048ecd79d08f721853409a44f0449438bc2c2",
-               "bytes": (37009700 * 2.0 + 88064) * 1024},
-    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "021c3339f721ba7bacecafc3bc608e59d0edb8307e2673071fa1762e4faa73b7",
-               "bytes": (2 * (44423.5 * 2.0 + 88070.0) + (44526.5 * 2.0 + 88065.0)) * 1024},
+    "stage1": {"sources": ("calib.hip",), "sha256": "b0918102597197e7091b75d88addc3f28c92ae6d61cf53cde2eacc16e9ed6c73",
+               "bytes": (42576600 * 2.0 + 88064) * 1024},
+    # the step's two batched launches: Gate + Up, Down
+    "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "59a2ddf16cfc324fc9097880e39ca2c036a6a5ac0261dfce7b7d1d9f3f26e98c",
+               "bytes": ((88443.7 * 2.0 + 176132.0) + (44497.5 * 2.0 + 88070.8)) * 1024},
 }
 
 
