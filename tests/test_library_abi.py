@@ -38,6 +38,20 @@ def test_workspace_queries(lib):
     assert lib.dass_nm_workspace_bytes(11008, 4096, 0) >= 4 * 11008
     assert lib.dass_nm_workspace_bytes(4096, 11008, 1) >= 4 * 11008
     assert lib.dass_unstructured_workspace_bytes(4096, 14336, 1, 1, 1) >= 4 * 14336
+    # column lines of a large matrix: the counts and lists of the passes over 64-column tiles
+    # (16-bit counts of 258 slots per column and row slab, 256 list entries of 16 bytes per column)
+    tiled = lib.dass_unstructured_workspace_bytes(11008, 4096, 1, 0, 0)
+    assert tiled >= 4 * 11008 + 4096 * (8 * 258 * 2 + 256 * 16)
+    assert tiled < 64 << 20
+    # a factor that does not vary along the column lines takes other kernels: the factor vector and little more
+    assert lib.dass_unstructured_workspace_bytes(11008, 4096, 1, 1, 0) < 1 << 20
+    # row lines: the factor vector, the flag block, one word per block of rows
+    rows = lib.dass_unstructured_workspace_bytes(4096, 11008, 1, 1, 1)
+    assert 4 * 11008 + 4096 // 8 * 4 <= rows < 1 << 20
+    # a small matrix: the factor vector and the flag block
+    assert lib.dass_unstructured_workspace_bytes(64, 64, 1, 0, 0) <= 1024
+    # column lines too long for one workgroup's registers, factor across them: the transposed copy
+    assert lib.dass_unstructured_workspace_bytes(24576, 3072, 1, 1, 0) >= 24576 * 3072 * 2
 
 
 FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: every call below is rejected first
