@@ -81,3 +81,56 @@ def test_pruning_step_replayed_from_a_graph(gpu_device):
         got_in = check(f"replay {replay}")
         # the pass without atomics gives the same bits every time
         assert torch.equal(got_in.view(torch.int32), eager_in.view(torch.int32))
+
+
+def test_unstructured_selection_replayed_from_a_graph(gpu_device):
+    """The per-line unstructured selection of a large Gate-Proj-shaped and Down-Proj-shaped matrix (the
+    passes over 64-column tiles: six launches that hand results to one another through the workspace,
+    and the one-launch row-line kernel, each followed by its gated second try) captured and replayed;
+    among the matrices one that the passes hand over to the second try (a column of equal scores)."""
+    dev = gpu_device
+    d, d_int = 1032, 2048
+    g = torch.Generator(device="cpu").manual_seed(33)
+    Wg0 = (torch.randn((d_int, d), generator=g) * 0.02).to(torch.bfloat16)
+    Wd0 = (torch.randn((d, d_int), generator=g) * 0.02).to(torch.bfloat16)
+    Wt0 = Wg0.clone()
+    Wt0[:, 3] = 0.25                                   # equal scores wherever the norms are equal
+    norms = (torch.rand(d_int, generator=g) * 30 + 0.01)
+    norms_t = norms.clone()
+    norms_t[: d_int // 2] = 4.0
+    Wg0, Wd0, Wt0, norms, norms_t = (t.to(dev) for t in (Wg0, Wd0, Wt0, norms, norms_t))
+    Wg, Wd, Wt = Wg0.clone(), Wd0.clone(), Wt0.clone()
+    ws = [torch.empty(dass.unstructured_workspace_bytes(*w.shape, w.dtype, axis, axis), dtype=torch.uint8, device=dev)
+          for w, axis in ((Wg, "rows"), (Wd, "cols"), (Wt, "rows"))]
+
+    def step():
+        Wg.copy_(Wg0)
+        Wd.copy_(Wd0)
+        Wt.copy_(Wt0)
+        dass.score_mask_unstructured(Wg, norms, "rows", "rows", 0.5, d_int // 2, workspace=ws[0])
+        dass.score_mask_unstructured(Wd, norms, "cols", "cols", 1.0, d_int // 2, workspace=ws[1])
+        dass.score_mask_unstructured(Wt, norms_t, "rows", "rows", 1.0, d_int // 2, workspace=ws[2])
+
+    want = [oracle.mask_unstructured(to_np32(w0), n.cpu().numpy(), axis, axis, alpha, d_int // 2)[0]
+            for w0, n, axis, alpha in ((Wg0, norms, "rows", 0.5), (Wd0, norms, "cols", 1.0), (Wt0, norms_t, "rows", 1.0))]
+
+    def check(tag):
+        for w, ref in zip((Wg, Wd, Wt), want):
+            assert bits_equal(w, ref), f"{tag}: {first_mismatch(w, ref)}"
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    side.synchronize()
+    check("eager")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(3):
+        for t in (Wg, Wd, Wt, *ws):                      # eager work between the replays
+            t.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(f"replay {replay}")
