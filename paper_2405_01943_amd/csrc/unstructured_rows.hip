@@ -7,9 +7,12 @@
 // term p, 256 bins inside it, the threshold's bin, an apply pass that lists the few scores inside
 // that bin, a ranking of the list - with whole lines owned by one workgroup: nothing is merged
 // between workgroups, so all of it is ONE launch.  A workgroup of 1024 threads takes 8 rows and
-//   0  computes the scaled factors of all columns into LDS,
+//   0  clears its counters,
 //   A  samples 128 positions of each row (one wavefront per row): the row's window,
-//   B  streams its rows (read 1) and counts into 8 x 258 LDS counters,
+//   B  streams its rows (read 1) and counts into 8 x 256 LDS bins (+ side counters); the scaled
+//      factors of the columns are computed into LDS first - all of them if 44 KB hold them,
+//      else chunk by chunk of columns, each chunk ahead of the part of the rows that needs it,
+//      so that two workgroups fit a compute unit's LDS whatever the line length,
 //   C  finds each row's bin (one wavefront per row),
 //   D  streams its rows again (read 2, out of the memory-side cache), zeroes what lies below the
 //      bin, writes whole lines once, and lists the scores inside the bin in LDS,
@@ -42,6 +45,11 @@ constexpr uint32_t kInfBits = 0x7f800000u;
 struct Window {
     uint32_t lo, sh;
 };
+// The columns are taken in `count` chunks of `vecs` 16-byte vectors (the last one `last_vecs`); the
+// magic numbers are ceil(2^32 / vecs) and ceil(2^32 / last_vecs) for the division by multiply-high.
+struct Chunks {
+    uint32_t count, vecs, last_vecs, magic, last_magic;
+};
 struct Select {
     uint32_t lo, width, need, inside;
 };
@@ -68,12 +76,12 @@ __device__ __forceinline__ uint32_t sample_run(uint32_t k, uint32_t cols)
 struct Smem {
     size_t fs, hist, list, cnt, win, sel, fail, bytes;
 };
-__host__ __device__ inline Smem smem_layout(uint32_t cols)
+__host__ __device__ inline Smem smem_layout(uint32_t chunk_cols)
 {
     Smem m;
     size_t off = 0;
     m.fs = off;
-    off += ((size_t)cols * 4 + 15) / 16 * 16;
+    off += ((size_t)chunk_cols * 4 + 15) / 16 * 16;
     // the counters are dead once the bins are found (phase C), the lists are filled after that: one place for both
     m.hist = m.list = off;
     off += (size_t)kRows * (kCap * 12 > kStride * 4 ? kCap * 12 : kStride * 4);
@@ -93,13 +101,13 @@ __host__ __device__ inline Smem smem_layout(uint32_t cols)
 template <int DT, bool MASK>
 __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ Wv, uint32_t rows, uint32_t cols,
                                                             int64_t ld, const float *__restrict__ norms, int fmode,
-                                                            uint32_t n_keep, uint32_t vpl_magic,
+                                                            uint32_t n_keep, const Chunks ck,
                                                             uint8_t *__restrict__ mask, uint32_t *__restrict__ todo)
 {
     constexpr int EPV = DT == DASS_BF16 ? 8 : 4;
     constexpr int EB = DT == DASS_BF16 ? 2 : 4;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const Smem m = smem_layout(cols);
+    const Smem m = smem_layout(ck.vecs * EPV);
     float *fs = reinterpret_cast<float *>(smem + m.fs);
     uint32_t *hist = reinterpret_cast<uint32_t *>(smem + m.hist);
     uint32_t *list = reinterpret_cast<uint32_t *>(smem + m.list);   // [kRows][kCap][3]
@@ -113,7 +121,6 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
     const uint32_t n_rows = rows - row0 < (uint32_t)kRows ? rows - row0 : (uint32_t)kRows;
     char *W = static_cast<char *>(Wv) + (size_t)row0 * ld * EB;
     const uint32_t row_bytes = (uint32_t)ld * EB;   // the block's 8 rows span less than 4 GB (host check)
-    const uint32_t vpl = cols / EPV, total = n_rows * vpl;   // vectors per line, per block
 
     // the rows' samples (phase A, one wavefront per row) are fetched first: they are on their way
     // while phase 0 runs.  Their factors come straight from the norms.
@@ -134,19 +141,7 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
         smp_n[1] = n2.y;
     }
 
-    // ---- 0: scaled factors of every column, counters cleared
-    bool bad = false;
-    for (uint32_t j = 4 * tid; j < cols; j += 4 * kThreads) {   // cols is a multiple of 8; norms are 16-byte aligned
-        const u32x4 n4 = *reinterpret_cast<const u32x4 *>(norms + j);
-        u32x4 f4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float f = factor_of(__uint_as_float(n4[i]), fmode);
-            bad |= !factor_in_fast_range(f);
-            f4[i] = __float_as_uint(f * kFactorScale);
-        }
-        *reinterpret_cast<u32x4 *>(fs + j) = f4;
-    }
+    // ---- 0: counters cleared
     for (int i = tid; i < kRows * kStride; i += kThreads)
         hist[i] = 0;
     if (tid < kRows)
@@ -154,8 +149,6 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
     if (tid == 0)
         *fail = 0;
     __syncthreads();
-    if (bad)
-        *fail = 1;
 
     // ---- A: the rows' windows, one wavefront per row
     if ((uint32_t)wave < n_rows) {
@@ -190,11 +183,28 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
     }
     __syncthreads();
 
-    // Vector v of the block's flat list -> (row, vector inside the row); v < 2^16 and vpl < 2^16, so the
-    // multiply-high by ceil(2^32 / vpl) is the exact quotient.
-    auto split = [&](uint32_t v, uint32_t &row, uint32_t &cv) {
-        row = __umulhi(v, vpl_magic);
-        cv = v - row * vpl;
+    // Scaled factors of chunk ch into LDS (cols is a multiple of 8, norms are 16-byte aligned).  The
+    // barriers around it are the caller's.
+    bool bad = false;
+    auto stage = [&](uint32_t ch) {
+        const uint32_t c_begin = ch * ck.vecs * EPV, n = (ch == ck.count - 1 ? ck.last_vecs : ck.vecs) * EPV;
+        for (uint32_t j = 4 * tid; j < n; j += 4 * kThreads) {
+            const u32x4 n4 = *reinterpret_cast<const u32x4 *>(norms + c_begin + j);
+            u32x4 f4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float f = factor_of(__uint_as_float(n4[i]), fmode);
+                bad |= !factor_in_fast_range(f);
+                f4[i] = __float_as_uint(f * kFactorScale);
+            }
+            *reinterpret_cast<u32x4 *>(fs + j) = f4;
+        }
+    };
+    // Vector v of a chunk's flat list (the block's rows x the chunk's vectors) -> (row, vector inside the
+    // chunk); v < 2^17 and the divisor < 2^14, so the multiply-high by ceil(2^32 / divisor) is the exact quotient.
+    auto split = [&](uint32_t v, uint32_t n_vecs, uint32_t magic, uint32_t &row, uint32_t &cv) {
+        row = __umulhi(v, magic);
+        cv = v - row * n_vecs;
     };
     auto factors = [&](uint32_t cv, float *f) __attribute__((always_inline)) {
 #pragma unroll
@@ -208,6 +218,13 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
 
     // ---- B: counts
     uint32_t a_max = 0;
+    for (uint32_t ch = 0; ch < ck.count; ++ch) {
+    const uint32_t n_vecs = ch == ck.count - 1 ? ck.last_vecs : ck.vecs, magic = ch == ck.count - 1 ? ck.last_magic : ck.magic;
+    const uint32_t total = n_rows * n_vecs, chunk_bytes = ch * ck.vecs * 16;
+    if (ch > 0)
+        __syncthreads();   // the previous chunk's factors are no longer read
+    stage(ch);
+    __syncthreads();
     for (uint32_t v0 = tid; v0 < total; v0 += kU * kThreads) {
         u32x4 x[kU];
 #pragma unroll
@@ -215,8 +232,8 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
             const uint32_t v = v0 + u * kThreads;
             if (v < total) {
                 uint32_t row, cv;
-                split(v, row, cv);
-                x[u] = *reinterpret_cast<const u32x4 *>(W + row * row_bytes + cv * 16);
+                split(v, n_vecs, magic, row, cv);
+                x[u] = *reinterpret_cast<const u32x4 *>(W + row * row_bytes + chunk_bytes + cv * 16);
             }
         }
 #pragma unroll
@@ -225,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
             __builtin_amdgcn_sched_barrier(0);   // moves up past this line
             if (v0 + u * kThreads < total) {
                 uint32_t row, cv;   // again, rather than kept in registers across the loads
-                split(v0 + u * kThreads, row, cv);
+                split(v0 + u * kThreads, n_vecs, magic, row, cv);
                 float f[EPV];
                 factors(cv, f);
                 const Window w = win[row];
@@ -241,7 +258,8 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
             }
         }
     }
-    if (a_max >= kInfBits)   // a product that overflowed
+    }
+    if (bad || a_max >= kInfBits)   // a factor outside the range of the two-term score, a product that overflowed
         *fail = 1;
     __syncthreads();
 
@@ -300,6 +318,14 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
     }
 
     // ---- D: apply and list
+    for (uint32_t ch = 0; ch < ck.count; ++ch) {
+    const uint32_t n_vecs = ch == ck.count - 1 ? ck.last_vecs : ck.vecs, magic = ch == ck.count - 1 ? ck.last_magic : ck.magic;
+    const uint32_t total = n_rows * n_vecs, chunk_bytes = ch * ck.vecs * 16, chunk_vec0 = ch * ck.vecs;
+    if (ck.count > 1) {   // one chunk: the factors are still there
+        __syncthreads();
+        stage(ch);
+        __syncthreads();
+    }
     for (uint32_t v0 = tid; v0 < total; v0 += kUD * kThreads) {
         u32x4 x[kUD];
 #pragma unroll
@@ -307,8 +333,9 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
             const uint32_t v = v0 + u * kThreads;
             if (v < total) {
                 uint32_t row, cv;
-                split(v, row, cv);
-                x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + row * row_bytes + cv * 16));
+                split(v, n_vecs, magic, row, cv);
+                x[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(W + row * row_bytes + chunk_bytes + cv * 16));
             }
         }
 #pragma unroll
@@ -318,7 +345,7 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
             __builtin_amdgcn_sched_barrier(0);   // moves up past this line
             uint32_t kept = 0, row = 0, cv = 0;
             if (live)
-                split(v0 + u * kThreads, row, cv);
+                split(v0 + u * kThreads, n_vecs, magic, row, cv);
             if (live) {
                 float f[EPV];
                 factors(cv, f);
@@ -345,26 +372,27 @@ __global__ __launch_bounds__(kThreads) void rowlines_kernel(void *__restrict__ W
                         uint32_t *entry = list + (row * kCap + slot) * 3;
                         entry[0] = __float_as_uint(p);
                         entry[1] = mono(fmaf(w, fe, -p));
-                        entry[2] = 0xFFFFu - (cv * EPV + e);
+                        entry[2] = 0xFFFFu - ((chunk_vec0 + cv) * EPV + e);
                     }
                 }
 #pragma unroll
                 for (int e = 0; e < EPV; ++e)
                     zero_lane_if<DT>(x[u], e, ((kept >> e) & 1u) == 0);
-                __builtin_nontemporal_store(x[u], reinterpret_cast<u32x4 *>(W + row * row_bytes + cv * 16));
+                __builtin_nontemporal_store(x[u], reinterpret_cast<u32x4 *>(W + row * row_bytes + chunk_bytes + cv * 16));
             }
             if constexpr (MASK) {
                 if constexpr (EPV == 8) {
                     if (live)
-                        mask[(size_t)(row0 + row) * (cols / 8) + cv] = (uint8_t)kept;
+                        mask[(size_t)(row0 + row) * (cols / 8) + chunk_vec0 + cv] = (uint8_t)kept;
                 } else {
                     // f32: a mask byte covers two neighbouring lanes' vectors (vpl is even, the two share every branch)
                     const uint32_t other = __shfl_xor(kept, 1, 64);
                     if (live && (cv & 1) == 0)
-                        mask[(size_t)(row0 + row) * (cols / 8) + cv / 2] = (uint8_t)(kept | other << 4);
+                        mask[(size_t)(row0 + row) * (cols / 8) + (chunk_vec0 + cv) / 2] = (uint8_t)(kept | other << 4);
                 }
             }
         }
+    }
     }
     // The 2-byte stores of E go to lines written just above by other wavefronts of this workgroup.  The
     // barrier orders them: it carries a workgroup-scope release (every store above has been accepted by
@@ -441,9 +469,10 @@ RowlinesPlan plan_rowlines(int64_t rows, int64_t cols, int64_t ld, int dt, const
     if (cols < 1024 || cols > 0xFFFF || cols % 8 != 0 || rows * cols < (1LL << 21) ||
         (int64_t)kRows * ld * elem_bytes(dt) >= (1LL << 32))
         return p;
-    p.smem = smem_layout((uint32_t)cols).bytes;
-    if (p.smem > 160 * 1024)
-        return p;
+    // columns in chunks of at most 11264 (44 KB of factors: with the lists, two workgroups per compute unit)
+    p.chunks = (int)((cols + 11263) / 11264);
+    p.chunk_cols = (cols / 8 + p.chunks - 1) / p.chunks * 8;
+    p.smem = smem_layout((uint32_t)p.chunk_cols).bytes;
     p.blocks = (rows + kRows - 1) / kRows;
     if (p.blocks > 0x7fffffffLL)
         return p;
@@ -464,9 +493,14 @@ dass_status launch_rowlines(const char *fn, const RowlinesPlan &p, void *W, int6
         hipSuccess)
         return fail(DASS_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, p.smem);
     const uint32_t vpl = (uint32_t)(cols / vec_elems(dt));
-    const uint32_t magic = (uint32_t)(((1ULL << 32) + vpl - 1) / vpl);
+    Chunks ck;
+    ck.count = (uint32_t)p.chunks;
+    ck.vecs = (uint32_t)(p.chunk_cols / vec_elems(dt));
+    ck.last_vecs = vpl - (ck.count - 1) * ck.vecs;
+    ck.magic = (uint32_t)(((1ULL << 32) + ck.vecs - 1) / ck.vecs);
+    ck.last_magic = (uint32_t)(((1ULL << 32) + ck.last_vecs - 1) / ck.last_vecs);
     hipLaunchKernelGGL(k, dim3((unsigned)p.blocks), dim3(kThreads), p.smem, stream, W, (uint32_t)rows, (uint32_t)cols, ld,
-                       norms, fmode, n_keep, magic, mask_out, todo);
+                       norms, fmode, n_keep, ck, mask_out, todo);
     return check_launch("row-line unstructured kernel");
 }
 

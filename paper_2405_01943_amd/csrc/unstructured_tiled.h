@@ -38,6 +38,8 @@ constexpr int kRowlinesBlock = 8;
 struct RowlinesPlan {
     bool fits;
     int64_t blocks;      // workgroups = blocks of kRowlinesBlock rows
+    int chunks;          // the columns' factors are staged in LDS in so many chunks ...
+    int64_t chunk_cols;  // ... of so many columns (a multiple of 8; the last chunk may be shorter)
     size_t smem;         // dynamic LDS of the kernel
     size_t todo_bytes;   // one word per block in the caller's workspace
 };

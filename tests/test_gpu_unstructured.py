@@ -382,12 +382,15 @@ def _rowline_todo(workspace, n_norms, rows):
 
 
 @pytest.mark.parametrize("dtype,rows,cols,pad", [(torch.bfloat16, 1032, 2048, 0), (torch.bfloat16, 520, 4104, 8),
-                                                 (torch.float32, 837, 2504, 4), (torch.bfloat16, 2052, 1024, 0)])
+                                                 (torch.float32, 837, 2504, 4), (torch.bfloat16, 2052, 1024, 0),
+                                                 (torch.bfloat16, 84, 28672, 0), (torch.float32, 132, 16392, 4),
+                                                 (torch.bfloat16, 68, 40000, 8), (torch.bfloat16, 188, 11272, 0)])
 def test_unstructured_row_lines_streamed(gpu_device, dtype, rows, cols, pad):
     """Row lines of matrices large enough for the one-launch streaming kernel (a workgroup owns 8 whole
     rows: window, counts, bin, apply with the bin's scores listed, ranking): a ragged last block of
-    rows, lines that are no multiple of the workgroup's stride, a leading dimension, both exponents,
-    quotas from a tenth to nine tenths and one from either end; mask bits as well."""
+    rows, lines that are no multiple of the workgroup's stride, lines so long that their factors are
+    staged in two, three or four chunks of columns, a leading dimension, both exponents, quotas from
+    a tenth to nine tenths and one from either end; mask bits as well."""
     g = torch.Generator(device="cpu").manual_seed(rows * 7 + cols)
     W0 = (torch.randn((rows, cols), generator=g) * 0.02).to(dtype)
     W0[5, :] *= 40.0                                  # rows of very different scale
