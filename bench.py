@@ -450,7 +450,7 @@ def main():
         oc = synth.CONFIGS[name]
         onk, om = oc.nm[0]
         oX, oWg, oWu, oWd = make_inputs(oc, dev)
-        o_ms, o_s1, o_s2, _ = run_steps(oc, onk, om, oX, oWg, oWu, oWd, args.other_steps, 1)
+        o_ms, o_s1, o_s2, o_norms = run_steps(oc, onk, om, oX, oWg, oWu, oWd, args.other_steps, 1)
         o_esz = 2 if oc.dtype == "bf16" else 4
         o_flops = 4.0 * oc.tokens * oc.d * oc.d_int
         o_bytes = 3 * 2.0 * oWd.numel() * o_esz
@@ -461,7 +461,22 @@ def main():
                        "stage1_frac": (o_flops / (o_s1 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if oc.dtype == "bf16" else None,
                        "stage2_us_3_matrices": o_s2 * 1e3, "stage2_GBps": o_bytes / (o_s2 * 1e-3) / 1e9,
                        "stage2_frac": o_bytes / (o_s2 * 1e-3) / 1e9 / PEAK_HBM_GBS})
-        del oX, oWg, oWu, oWd
+        if oc.unstructured is not None:   # the configuration's unstructured variant, launch by launch on cold copies
+            o_prune = int(round(oc.unstructured * oc.d_int))
+            o_mat = 2.0 * oWd.numel() * o_esz
+            o_copies = max(2, int(320e6 // (oWd.numel() * o_esz)) + 1)
+            o_ws = torch.empty(max(16, dass.unstructured_workspace_bytes(oc.d_int, oc.d, oWg.dtype, "rows", "rows"),
+                                   dass.unstructured_workspace_bytes(oc.d, oc.d_int, oWd.dtype, "cols", "cols")),
+                               dtype=torch.uint8, device=dev)
+            o_u = {"n_prune_per_line": o_prune, "bytes_per_matrix": o_mat}
+            for key, W0, axis, alpha in (("gate", oWg, "rows", oc.alpha_gate_up), ("down", oWd, "cols", oc.alpha_down)):
+                c = cold_launch_us(W0, lambda w: dass.score_mask_unstructured(w, o_norms, axis, axis, alpha, o_prune,
+                                                                              workspace=o_ws), 8, o_copies)
+                o_u[key] = dict(c, GBps=o_mat / (c["median_us"] * 1e-6) / 1e9,
+                                frac=o_mat / (c["median_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
+            others[-1]["unstructured"] = o_u
+            del o_ws
+        del oX, oWg, oWu, oWd, o_norms
         torch.cuda.empty_cache()
 
     out = {
