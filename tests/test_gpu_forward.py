@@ -76,7 +76,7 @@ def test_forward_token_chunks_are_independent(gpu_device):
 
 def test_forward_full_size_with_pruned_weights(gpu_device):
     """The LLaMA2-7B-shaped MLP with DaSS 2:4 weights on a 32768-token chunk of the calibration
-    set (the launch shape the benchmark times), checked on sampled tokens: all d outputs of the
+    set, y in a workspace the binding allocates, checked on sampled tokens: all d outputs of the
     first and last token, of both sides of tile boundaries and of seeded random ones."""
     cfg = synth.CONFIGS["llama2_7b"]
     dev = gpu_device
@@ -97,6 +97,51 @@ def test_forward_full_size_with_pruned_weights(gpu_device):
                                  to_np32(Wd), cfg.act, want_abs=True)
     _check(to_np32(out[torch.as_tensor(tokens, device=dev)]), ref, ab, "7B shape, 2:4 weights")
     assert torch.isfinite(out.float()).all()
+
+
+def test_forward_at_the_benchmark_token_count(gpu_device):
+    """One call over all 262144 calibration tokens of the LLaMA2-7B-shaped MLP with DaSS 2:4 weights,
+    as the benchmark times it (y, 5.7 GB, in the caller's workspace), and Eq. 3 again from the
+    compressed Down-Proj over the same tokens; sampled tokens: the ends, both sides of tile
+    boundaries at the start, the middle and the end of the token range, and seeded random ones."""
+    cfg = synth.CONFIGS["llama2_7b"]
+    dev = gpu_device
+    T, d, d_int = cfg.tokens, cfg.d, cfg.d_int
+    assert T == 262144
+    X = synth.make_x(cfg, 0, T, dev)
+    Wg, Wu, Wd = (synth.make_weight(cfg, w, dev) for w in ("wg", "wu", "wd"))
+    norms = synth.make_norms(d_int, dev)
+    dass.score_mask_nm(Wg, norms, "rows", "rows", 0.5, 2, 4)
+    dass.score_mask_nm(Wu, norms, "rows", "rows", 0.5, 2, 4)
+    dass.score_mask_nm(Wd, norms, "cols", "cols", 1.0, 2, 4)
+    out = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(dass.mlp_forward_workspace_bytes(T, d, d_int), dtype=torch.uint8, device=dev)
+    dass.mlp_forward(X, Wg, Wu, Wd, cfg.act, out, workspace=ws)
+    values = torch.empty((d, d_int // 2), dtype=Wd.dtype, device=dev)
+    meta = torch.empty((d, d_int // 8), dtype=torch.uint8, device=dev)
+    dass.compress_24(Wd, "cols", values, meta)
+    Y = ws.view(torch.bfloat16).view(T, d_int)
+    out3 = torch.empty_like(out)
+    dass.down_proj_sparse24(Y, values, meta, out3)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    tokens = np.unique(np.concatenate([[0, 255, 256, 1023, 1024, T // 2 - 1, T // 2, T - 1025, T - 1024, T - 257,
+                                        T - 256, T - 1], rng.integers(0, T, size=12)]))
+    sel = torch.as_tensor(tokens, device=dev)
+    ref, ab = oracle.mlp_forward(to_np32(X[sel]), to_np32(Wg), to_np32(Wu), to_np32(Wd), cfg.act, want_abs=True)
+    _check(to_np32(out[sel]), ref, ab, "7B shape, 2:4 weights, 262144 tokens")
+    ref3, ab3 = oracle.down_sparse24(to_np32(Y[sel]), to_np32(values), meta.cpu().numpy(), want_abs=True)
+    err = np.abs(to_np32(out3[sel]).astype(np.float64) - ref3) / (2.0 ** -8 * (np.abs(ref3) + 0.5 * ab3) + 1e-30)
+    assert float(err.max()) <= 1.0, f"sparse route at {err.max():.2f} of its tolerance"
+    # every token was written: the two routes agree to bf16 rounding everywhere (they round y alike and
+    # differ in the order of the f32 sums only)
+    step = 4096
+    for lo in range(0, T, step):
+        a, b = out[lo:lo + step].float(), out3[lo:lo + step].float()
+        assert torch.isfinite(a).all() and torch.isfinite(b).all()
+        scale = a.abs().mean().item()
+        assert scale > 0.0
+        assert (a - b).abs().mean().item() <= 0.02 * scale, f"tokens {lo}..{lo + step}: the two routes differ"
 
 
 @pytest.mark.parametrize("name", ["mistral_7b", "gemma_7b", "llama2_13b", "llama2_70b"])
