@@ -577,8 +577,15 @@ TiledPlan plan_tiled(int64_t rows, int64_t cols, int64_t ld, int dt, const uint8
         rows * ld * elem_bytes(dt) >= (1LL << 40))
         return p;
     p.groups = (cols + kCols - 1) / kCols;
-    // about two workgroups per compute unit, slabs of at least 256 rows
-    int64_t slabs = (512 + p.groups - 1) / p.groups;
+    // One workgroup per compute unit (256 of them) and never a few left over for a second round; two
+    // per compute unit where a workgroup would otherwise stream more than 8192 rows (measured: 7B
+    // 87 -> 83 us, Gemma-7B 167 -> 155 us with one, the 70B layer 425 -> 415 us with two).  Fewer slabs
+    // also mean fewer counts to write and to add up.  Slabs of at least 256 rows.
+    int64_t slabs = 256 / p.groups;
+    if (slabs < 1)
+        slabs = 1;
+    if (rows / slabs > 8192 && 512 / p.groups > slabs)
+        slabs = 512 / p.groups;
     if (slabs > rows / 256)
         slabs = rows / 256;
     if (slabs < 1)
