@@ -202,7 +202,7 @@ def cpu_baseline(cfg, n_keep, m, Wg, Wu, Wd, X_sample, norms32):
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU only; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
