@@ -316,11 +316,13 @@ __global__ __launch_bounds__(256) void scan_kernel(const uint16_t *__restrict__ 
 // ------------------------------------------------------------------- apply --
 // Nothing is shared between rows here, so the matrix is covered by many small workgroups whose
 // threads make one trip each (streams faster than resident workgroups that loop): 256 threads take
-// 8 row blocks of a tile, a thread one 16-byte vector of each.  A score inside its column's bin
+// 4 row blocks of a tile, a thread one 16-byte vector of each (measured, a whole 7B model's 96
+// matrices one after the other: 7.35 ms with 3 or 4 vectors per thread, 7.45 with 2, 7.5 with 6,
+// 7.6 with 8).  A score inside its column's bin
 // is rare (a few dozen per column): the workgroup gathers them in LDS (up to kLocal per column)
 // and moves them to the columns' lists at the end, one global counter update per column; what
 // does not fit goes to the list directly.
-constexpr int kApplyThreads = 256, kApplyTrips = 8, kLocal = 8;
+constexpr int kApplyThreads = 256, kApplyTrips = 4, kLocal = 8;
 
 template <int DT, bool MASK>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__ Wv, uint32_t rows, uint32_t cols,
