@@ -20,6 +20,9 @@
  *   - Inputs must be finite.  The result for NaN or Inf inputs is undefined.
  *   - Thread safe; the only library state is a thread-local error string
  *     (and, for dass_score_mask_unstructured_static, one device array).
+ *     Calls enqueued on different streams may run at the same time as long
+ *     as no buffer one of them writes (its matrix, outputs, workspace) is
+ *     used by another; a call's several launches are ordered by its stream.
  */
 #ifndef DASS_H
 #define DASS_H

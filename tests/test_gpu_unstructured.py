@@ -456,6 +456,49 @@ def test_unstructured_row_lines_streamed_undecided_cases(gpu_device):
     check(W.to(gpu_device), synth.make_norms(cols, "cpu", 4).to(gpu_device), 0.5, cols // 2, "ordinary again", set())
 
 
+def test_unstructured_calls_overlap_on_several_streams(gpu_device):
+    """Twelve selections (column lines by tiles, row lines in one launch, and a matrix that the
+    streaming passes hand on to the second try) dealt to four streams of the caller's, a workspace
+    per stream: the calls share nothing else, so they may run at the same time, and every result
+    is the oracle's."""
+    dev = gpu_device
+    d, d_int = 1032, 2048
+    g = torch.Generator(device="cpu").manual_seed(77)
+    cases = []
+    for k in range(12):
+        kind = ("gate", "down", "gate", "ties")[k % 4]
+        if kind == "down":
+            W0 = (torch.randn((d, d_int), generator=g) * 0.02).to(torch.bfloat16)
+            axis, alpha = "cols", 1.0
+        else:
+            W0 = (torch.randn((d_int, d), generator=g) * 0.02).to(torch.bfloat16)
+            axis, alpha = "rows", 0.5
+        nrm = synth.make_norms(d_int, "cpu", 100 + k)
+        if kind == "ties":
+            W0[:, 3] = 0.25
+            nrm[: d_int // 2] = 4.0          # a column of equal scores: more of them than a list holds
+        cases.append((W0, nrm, axis, alpha))
+    want = [oracle.mask_unstructured(to_np32(W0), nrm.numpy(), axis, axis, alpha, d_int // 2)[0]
+            for W0, nrm, axis, alpha in cases]
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    ws = [torch.empty(max(dass.unstructured_workspace_bytes(d_int, d, torch.bfloat16, "rows", "rows"),
+                          dass.unstructured_workspace_bytes(d, d_int, torch.bfloat16, "cols", "cols")),
+                      dtype=torch.uint8, device=dev) for _ in streams]
+    Ws = [W0.to(dev) for W0, _, _, _ in cases]
+    norms = [nrm.to(dev) for _, nrm, _, _ in cases]
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for W, (W0, _, _, _) in zip(Ws, cases):
+            W.copy_(W0)
+        torch.cuda.synchronize()
+        for k, (W, nrm, (_, _, axis, alpha)) in enumerate(zip(Ws, norms, cases)):
+            dass.score_mask_unstructured(W, nrm, axis, axis, alpha, d_int // 2, workspace=ws[k % 4],
+                                         stream=streams[k % 4])
+        torch.cuda.synchronize()
+        for k, (W, ref) in enumerate(zip(Ws, want)):
+            assert bits_equal(W, ref), f"round {rep}, call {k}: {first_mismatch(W, ref)}"
+
+
 def test_unstructured_argument_errors(gpu_device):
     W = torch.ones((8, 16), dtype=torch.bfloat16, device=gpu_device)
     nrm = torch.ones(16, device=gpu_device)
