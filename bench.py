@@ -280,7 +280,7 @@ def main():
                                   ("down", Wd, ("cols", "cols"), cfg.alpha_down)):
         c = cold_launch_us(W0, lambda w: dass.score_mask_unstructured(w, norms, axes[0], axes[1], alpha, I // 2,
                                                                       workspace=ws_u),
-                           max(6, args.stage2_launches // 2), n_copies)
+                           max(6, args.stage2_launches - 4), n_copies)
         unstructured[name] = dict(c, GBps=bytes_per_matrix / (c["median_us"] * 1e-6) / 1e9,
                                   frac=frac_of_hbm(c["median_us"]))
     unstructured["bound"] = "hbm"
@@ -488,7 +488,7 @@ def main():
             o_u = {"n_prune_per_line": o_prune, "bytes_per_matrix": o_mat}
             for key, W0, axis, alpha in (("gate", oWg, "rows", oc.alpha_gate_up), ("down", oWd, "cols", oc.alpha_down)):
                 c = cold_launch_us(W0, lambda w: dass.score_mask_unstructured(w, o_norms, axis, axis, alpha, o_prune,
-                                                                              workspace=o_ws), 8, o_copies)
+                                                                              workspace=o_ws), max(6, args.stage2_launches - 4), o_copies)
                 o_u[key] = dict(c, GBps=o_mat / (c["median_us"] * 1e-6) / 1e9,
                                 frac=o_mat / (c["median_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
             others[-1]["unstructured"] = o_u
