@@ -179,6 +179,44 @@ def test_config_stage2_full_size(gpu_device, name):
         print(f"[{name}] unstructured {cfg.unstructured:.0%} masks of gate/up/down bit-exact", flush=True)
 
 
+@pytest.mark.parametrize("name", ["llama2_7b", "gemma_7b", "llama2_13b", "llama2_70b"])
+def test_config_unstructured_full_size_sampled_lines(gpu_device, name):
+    """50 % unstructured masks of the full-size Gate-Proj and Down-Proj of the shapes whose configuration
+    names no unstructured variant (other counts of row slabs and column chunks than the Mistral shape's):
+    every line keeps exactly its quota, and sampled lines - the first and last, both sides of tile and
+    workgroup boundaries, seeded random ones - are the oracle's bit for bit (lines are independent, so
+    the oracle runs on the sampled lines alone)."""
+    cfg = synth.CONFIGS[name]
+    dev = gpu_device
+    d, I = cfg.d, cfg.d_int
+    norms = synth.make_norms(I, dev, seed=11)
+    n32 = norms.cpu().numpy()
+    n_prune = I // 2
+    rng = np.random.default_rng(5)
+    for which, axis, alpha, n_lines in (("wg", "rows", cfg.alpha_gate_up, d), ("wd", "cols", cfg.alpha_down, d)):
+        W0 = synth.make_weight(cfg, which, dev)
+        W = W0.clone()
+        dass.score_mask_unstructured(W, norms, axis, axis, alpha, n_prune)
+        torch.cuda.synchronize()
+        line_dim = 0 if axis == "rows" else 1
+        # (a weight that was zero before has the lowest score there is and is among the pruned ones)
+        zeros = (W == 0).sum(dim=line_dim)
+        assert int(zeros.min().item()) == n_prune and int(zeros.max().item()) == n_prune, \
+            f"{name} {which}: zeros per line {int(zeros.min().item())} .. {int(zeros.max().item())}, want {n_prune}"
+        kept_same = torch.where(W == 0, torch.zeros_like(W0), W0)
+        assert torch.equal(kept_same.view(torch.int16), W.view(torch.int16)), f"{name} {which}: a kept weight changed"
+        lines = np.unique(np.concatenate([[0, 1, 7, 8, 63, 64, 65, n_lines // 2 - 1, n_lines // 2, n_lines - 65,
+                                           n_lines - 64, n_lines - 9, n_lines - 8, n_lines - 1],
+                                          rng.integers(0, n_lines, size=18)]))
+        sel = torch.as_tensor(lines, device=dev)
+        sub0 = W0[:, sel] if axis == "rows" else W0[sel, :]
+        sub = W[:, sel] if axis == "rows" else W[sel, :]
+        want, _ = oracle.mask_unstructured(to_np32(sub0.contiguous()), n32, axis, axis, alpha, n_prune)
+        assert bits_equal(sub.contiguous(), want), f"{name} {which}: " + first_mismatch(sub.contiguous(), want)
+        del W0, W, kept_same
+    print(f"\n[{name}] unstructured 50 %: quotas of all lines, {lines.size} sampled lines per matrix bit-exact", flush=True)
+
+
 @pytest.mark.parametrize("alpha", [0.25, 0.5, 0.75, 1.0])
 def test_alpha_sweep_full_size_gate(gpu_device, alpha):
     """The exponents of the paper's ablation (Sec. 4.4) on one full-size Gate-Proj, 2:4, against the oracle.
