@@ -107,18 +107,21 @@ def run_steps(cfg, n_keep, m, X, Wg, Wu, Wd, steps, warmup):
 
     dev = X.device
     T, d, I = cfg.tokens, cfg.d, cfg.d_int
-    Wg_p, Wu_p, Wd_p = (torch.empty_like(w) for w in (Wg, Wu, Wd))
     sumsq = torch.empty(I, device=dev)
     norms = torch.empty(I, device=dev)
-    tasks = [(Wg_p, norms, "rows", "rows", cfg.alpha_gate_up), (Wu_p, norms, "rows", "rows", cfg.alpha_gate_up),
-             (Wd_p, norms, "cols", "cols", cfg.alpha_down)]
-    ws_nm = torch.empty(max(16, dass.nm_batched_workspace_bytes(tasks)), dtype=torch.uint8, device=dev)
+    # stage 2 works in place: every step prunes its own fresh copies of the three matrices, all of them
+    # resident before the timed region starts
+    fresh = [tuple(w.clone() for w in (Wg, Wu, Wd)) for _ in range(warmup + steps)]
+    task_sets = [[(g, norms, "rows", "rows", cfg.alpha_gate_up), (u, norms, "rows", "rows", cfg.alpha_gate_up),
+                  (dn, norms, "cols", "cols", cfg.alpha_down)] for g, u, dn in fresh]
+    ws_nm = torch.empty(max(16, dass.nm_batched_workspace_bytes(task_sets[0])), dtype=torch.uint8, device=dev)
     chunks = [(lo, min(cfg.chunk, T - lo)) for lo in range(0, T, cfg.chunk)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    todo = iter(task_sets)
 
     def step():
-        Wg_p.copy_(Wg); Wu_p.copy_(Wu); Wd_p.copy_(Wd)
+        tasks = next(todo)
         e = [ev() for _ in range(3)]
         e[0].record()
         for k, (lo, n) in enumerate(chunks):
