@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__
     __shared__ uint32_t base[kCols];
     __shared__ uint32_t held[kCols][kLocal][3];
     __shared__ uint2 bins[kCols];   // (lo, width) of the tile's columns
-    const uint32_t stop = *flag;
+    __shared__ uint32_t stop;       // the flag as one thread read it: the same answer for the whole workgroup
     const int tid = threadIdx.x;
     const uint32_t g = blockIdx.x % groups, block = blockIdx.x / groups;
     if (tid < kCols) {
@@ -346,6 +346,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__
         bins[tid] = make_uint2(t.lo, t.width);
         found[tid] = 0;
     }
+    if (tid == kCols)
+        stop = *flag;
     const uint32_t piece = tid % LPR, r0 = block * (U * RPI) + tid / LPR;
     const uint32_t c0 = g * kCols + piece * EPV;
     const bool active = c0 < cols;
@@ -360,9 +362,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(void *__restrict__
             f[u] = fs[ru];
         }
     }
-    if (stop)
-        return;   // the matrix is left as it was for the gated launches that follow (uniform)
     __syncthreads();
+    if (stop)
+        return;   // the matrix is left as it was for the gated launches that follow
     uint32_t lo[EPV], width[EPV];
 #pragma unroll
     for (int e = 0; e < EPV; ++e) {
