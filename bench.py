@@ -44,8 +44,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; see profiles/).  A figure only stands while the source
 # of its kernel is the one the counters were taken on; otherwise `traffic` is null.
 MEASURED_TRAFFIC = {
-    "stage1": {"sources": ("calib.hip",), "sha256": "b0918102597197e7091b75d88addc3f28c92ae6d61cf53cde2eacc16e9ed6c73",
-               "bytes": (42576600 * 2.0 + 88064) * 1024},
+    "stage1": {"sources": ("calib.hip",), "sha256": "32f3e49d551e12f84e1d9c3a627c4ffdcb1d80bd535600bb278f4661e9586e2c",
+               "bytes": (42365400 * 2.0 + 88064) * 1024},
     # the step's two batched launches: Gate + Up, Down
     "stage2": {"sources": ("nm.hip", "select.h"), "sha256": "59a2ddf16cfc324fc9097880e39ca2c036a6a5ac0261dfce7b7d1d9f3f26e98c",
                "bytes": ((88443.7 * 2.0 + 176132.0) + (44497.5 * 2.0 + 88070.8)) * 1024},

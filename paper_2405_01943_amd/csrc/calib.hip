@@ -358,10 +358,12 @@ constexpr int P64_LDS = 5 * 32768;
 enum { kEpiNorms = 0, kEpiGlu = 1, kEpiGemm = 2 };
 
 // float -> bf16 bits, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_bits(float x)
+// Two f32 rounded to bf16 (nearest even), `lo` in the low half of the word: one v_cvt_pk_bf16_f32.
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)
 {
-    const uint32_t b = __float_as_uint(x);
-    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 
 template <int ACT, int EPI>
@@ -665,7 +667,7 @@ __global__ __launch_bounds__(256) void calib_pipe64_kernel(
             const bool odd = fr & 1;
             const float mine = odd ? v1 : v0, send = odd ? v0 : v1;
             const float got = __shfl_xor(send, 1, 64);
-            const uint32_t word = odd ? bf16_bits(got) | bf16_bits(mine) << 16 : bf16_bits(mine) | bf16_bits(got) << 16;
+            const uint32_t word = odd ? bf16_pair(got, mine) : bf16_pair(mine, got);
             const int row = row_even + (odd ? 1 : 0), col = col_base + (fr & ~1);
             *reinterpret_cast<uint32_t *>(lds64 + row * SROW + col * 2) = word;
         };

@@ -53,10 +53,12 @@ __device__ __forceinline__ void block_barrier()
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
-__device__ __forceinline__ uint32_t bf16_bits(float x)   // round to nearest even, finite inputs
+// Two f32 rounded to bf16 (nearest even), `lo` in the low half of the word: one v_cvt_pk_bf16_f32.
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)
 {
-    const uint32_t b = __float_as_uint(x);
-    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 
 __global__ __launch_bounds__(256) void down_sparse24_kernel(
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(256) void down_sparse24_kernel(
             for (int g = 0; g < 4; ++g) {
                 const int token = wn * 128 + j * 32 + fr, feature = wm * 128 + i * 32 + 8 * g + 4 * fc;
                 u32x2 w;
-                w[0] = bf16_bits(acc[i][j][4 * g]) | bf16_bits(acc[i][j][4 * g + 1]) << 16;
-                w[1] = bf16_bits(acc[i][j][4 * g + 2]) | bf16_bits(acc[i][j][4 * g + 3]) << 16;
+                w[0] = bf16_pair(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
+                w[1] = bf16_pair(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
                 *reinterpret_cast<u32x2 *>(lds + token * SROW + feature * 2) = w;
             }
     __syncthreads();
